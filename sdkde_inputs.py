@@ -1,0 +1,93 @@
+"""Seeded synthetic workloads for the SD-KDE hot path.
+
+This module only draws inputs (samples, queries, bandwidth); it contains none of the
+estimator's arithmetic and is the single piece shared by the CPU oracle's tests and the
+HIP path's tests and benchmark.
+
+The paper's experiments use a "simple 16-D Gaussian mixture" with n_test = n_train/8
+(Results section) and a 1-D mixture (Appendix A) without stating their parameters; the
+mixtures below stand in for them.  The bandwidth follows Silverman's rule of thumb, which
+the paper names (Introduction) but does not spell out; the multivariate normal-reference
+form is used here.
+
+Draw order for a given seed (numpy Generator, PCG64), all in float64 then cast to fp32:
+  1. component means  K x d ~ N(0, 9)
+  2. (diagonal-covariance configs only) variances K x d ~ U[0.5, 2]
+  3. sample labels, 4. sample normals, 5. query labels, 6. query normals
+The 1-D config draws labels (Bernoulli 0.3) and normals for the samples only; its queries are
+a uniform grid.
+"""
+from __future__ import annotations
+
+import dataclasses
+import numpy as np
+
+
+@dataclasses.dataclass(frozen=True)
+class Config:
+    name: str
+    n: int
+    m: int
+    d: int
+    kind: str          # "mix_iso" | "mix_diag" | "mix_1d"
+    components: int
+
+
+CONFIGS = {
+    "C1": Config("C1", 4096, 1024, 16, "mix_iso", 4),
+    "C2": Config("C2", 32768, 32768, 16, "mix_iso", 4),
+    "C3": Config("C3", 32768, 65536, 1, "mix_1d", 2),
+    "C4": Config("C4", 262144, 65536, 64, "mix_diag", 8),
+    "C5": Config("C5", 1048576, 131072, 16, "mix_iso", 4),
+}
+
+
+def silverman_bandwidth(x: np.ndarray) -> float:
+    """Normal-reference rule: h = sigma * (4 / ((d + 2) n))^(1 / (d + 4)),
+    sigma^2 = mean over dimensions of the unbiased per-dimension sample variance."""
+    x = np.asarray(x, dtype=np.float64)
+    n, d = x.shape
+    sigma = float(np.sqrt(np.mean(np.var(x, axis=0, ddof=1))))
+    return sigma * (4.0 / ((d + 2.0) * n)) ** (1.0 / (d + 4.0))
+
+
+def _mixture(rng, count, means, variances):
+    k, d = means.shape
+    labels = rng.integers(0, k, size=count)
+    z = rng.standard_normal((count, d))
+    if variances is None:
+        return means[labels] + z
+    return means[labels] + z * np.sqrt(variances[labels])
+
+
+def gaussian_mixture(n: int, m: int, d: int, components: int = 4, seed: int = 0,
+                     diag_cov: bool = False):
+    """Equal-weight mixture; means ~ N(0, 9 I); unit covariance, or diagonal with variances
+    uniform on [0.5, 2] when diag_cov.  Returns (samples[n,d], queries[m,d], h) as fp32/fp32/float."""
+    rng = np.random.default_rng(seed)
+    means = 3.0 * rng.standard_normal((components, d))
+    variances = rng.uniform(0.5, 2.0, size=(components, d)) if diag_cov else None
+    x = _mixture(rng, n, means, variances).astype(np.float32)
+    q = _mixture(rng, m, means, variances).astype(np.float32)
+    return x, q, silverman_bandwidth(x)
+
+
+def mixture_1d(n: int, m: int, seed: int = 0, lo: float = -5.0, hi: float = 6.0):
+    """0.7 N(0,1) + 0.3 N(3, variance 0.25); queries on a uniform grid over [lo, hi]."""
+    rng = np.random.default_rng(seed)
+    second = rng.random(n) < 0.3
+    z = rng.standard_normal(n)
+    x = np.where(second, 3.0 + 0.5 * z, z).astype(np.float32).reshape(n, 1)
+    q = np.linspace(lo, hi, m).astype(np.float32).reshape(m, 1)
+    return x, q, silverman_bandwidth(x)
+
+
+def make(name: str, seed: int = 0, n: int | None = None, m: int | None = None):
+    """Inputs of a named config; n/m may be overridden to get a scaled-down case of the
+    same distribution."""
+    cfg = CONFIGS[name]
+    n = cfg.n if n is None else n
+    m = cfg.m if m is None else m
+    if cfg.kind == "mix_1d":
+        return mixture_1d(n, m, seed)
+    return gaussian_mixture(n, m, cfg.d, cfg.components, seed, diag_cov=(cfg.kind == "mix_diag"))
