@@ -1,0 +1,106 @@
+/*
+ * sdkde.h - C ABI of the MI355X (gfx950) SD-KDE library.
+ *
+ * The library computes the three steps of score-debiased kernel density estimation
+ * exactly as the paper states the problem (Introduction; Method section): samples x_i in
+ * R^d (n of them), a scalar bandwidth h, and query points y_j (m of them).
+ *
+ * Conventions for every call
+ *  - All array arguments are DEVICE pointers to fp32, row-major, contiguous, owned by the
+ *    caller.  The library never frees, retains or reallocates them.  `workspace` is device
+ *    memory too (any 256-byte aligned block of at least sdkde_workspace_bytes() bytes); its
+ *    contents are scratch and need no initialisation.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is only
+ *    enqueued; no call synchronises with the host, and no call allocates device memory.
+ *  - h is passed as double so that the derived constants are formed in double and rounded
+ *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation).
+ *  - Results are deterministic: no atomics are used, so repeated calls with the same
+ *    arguments give bit-identical outputs.
+ *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
+ *    are unspecified.  Two calls that share a workspace must be ordered on one stream.
+ */
+#ifndef SDKDE_H
+#define SDKDE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SDKDE_OK = 0,
+    SDKDE_EINVAL = 1,       /* null pointer, n < 1, m < 0, d < 1, h not finite or <= 0 */
+    SDKDE_EUNSUPPORTED = 2, /* d above SDKDE_MAX_D, unknown flag bits */
+    SDKDE_EWORKSPACE = 3,   /* workspace missing, misaligned or too small */
+    SDKDE_EDEVICE = 4       /* a HIP launch or event call failed */
+};
+
+enum {
+    SDKDE_MAX_D = 128,
+    SDKDE_PREC_FP32 = 0     /* flags bits 0-3: precision mode; only fp32 is defined */
+};
+
+/*
+ * Bytes of workspace sufficient for each of: sdkde_score at the n samples themselves,
+ * sdkde_score at m separate points, and sdkde_eval at m queries, all with n samples of
+ * dimension d.  One block of this size serves the whole score -> debias -> eval pipeline.
+ * bytes: host pointer, written on success.
+ */
+int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_t *bytes);
+
+/*
+ * Empirical score of the Gaussian KDE of `samples` with bandwidth h (Introduction, formula
+ * for s-hat; Method section, the identity that turns its numerator into T = Phi X):
+ *     s(p) = sum_j -(p - x_j) phi_j / (h^2 sum_j phi_j),  phi_j = exp(-|p - x_j|^2 / 2h^2),
+ * evaluated at each of the m `points`.  points == NULL means "at the samples themselves"
+ * (then m must equal n); the sum always runs over all n samples, so a point that is a
+ * sample includes its own term.  A point so far from every sample that all phi_j underflow
+ * in fp32 gets score 0.
+ *   samples   [n, d] in      points [m, d] in (or NULL)      score_out [m, d] out
+ * score_out must not overlap samples, points or workspace.
+ */
+int sdkde_score(const float *samples, int64_t n, const float *points, int64_t m, int32_t d,
+                double h, float *score_out, void *workspace, size_t workspace_bytes,
+                uint32_t flags, void *stream);
+
+/*
+ * Debiasing shift (Introduction; Method section): samples_sd = samples + (h^2 / 2) score,
+ * elementwise over [n, d].  samples_sd_out may alias samples or score.  n = 0 is a no-op.
+ */
+int sdkde_debias(const float *samples, const float *score, int64_t n, int32_t d, double h,
+                 float *samples_sd_out, void *stream);
+
+/*
+ * Gaussian KDE of `samples_sd` at the queries (Introduction, first display, with phi the
+ * standard normal density so that the estimate integrates to one; Method section, the
+ * train-query Gram matrix):
+ *     p(q) = 1 / (n h^d (2 pi)^(d/2)) * sum_j exp(-|q - x_j|^2 / 2h^2).
+ * density_out and log_density_out are [m] outputs; either may be NULL, not both.  The
+ * density underflows to 0 where it is below the fp32 range (large d); the log density is
+ * finite unless every term underflows in fp32 (then -inf).  m = 0 is a no-op.
+ *   samples_sd [n, d] in     queries [m, d] in
+ */
+int sdkde_eval(const float *samples_sd, int64_t n, const float *queries, int64_t m, int32_t d,
+               double h, float *density_out, float *log_density_out, void *workspace,
+               size_t workspace_bytes, uint32_t flags, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *sdkde_status_string(int status);
+
+/*
+ * Optional instrumentation.  While enabled, sdkde_score and sdkde_eval bracket their main
+ * pair-interaction kernel with HIP events on the caller's stream (up to 256 launches of each
+ * kind are kept; enabling or disabling resets the record).  sdkde_profile_summary waits for
+ * the recorded events of one kind (which: 0 = score, 1 = eval) and returns how many launches
+ * were recorded and the sum of their durations in milliseconds (host pointers).  The state is
+ * process-global and not thread-safe.
+ */
+int sdkde_profile_enable(int on);
+int sdkde_profile_summary(int which, int *launches, float *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SDKDE_H */

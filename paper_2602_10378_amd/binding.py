@@ -1,0 +1,169 @@
+"""Thin ctypes binding of libsdkde.so: argument marshalling only.
+
+Function names and argument order mirror include/sdkde.h.  Tensors must be CUDA(HIP) fp32 and
+contiguous; PyTorch supplies device memory and the stream, every arithmetic step runs inside
+the library's kernels.  A missing library is an error: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+from . import build as _build
+
+SDKDE_OK = 0
+SDKDE_PREC_FP32 = 0
+SDKDE_MAX_D = 128
+
+_lib = None
+
+
+class SdkdeError(RuntimeError):
+    def __init__(self, call: str, status: int, text: str):
+        super().__init__(f"{call} failed: status {status} ({text})")
+        self.status = status
+
+
+def load() -> ctypes.CDLL:
+    """Loads the built library (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = _build.LIBRARY
+    if not os.path.exists(path):
+        path = _build.build(force=True)
+    lib = ctypes.CDLL(path)
+    c_fp = ctypes.c_void_p
+    i64, i32, u32, f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_double
+    lib.sdkde_workspace_bytes.argtypes = [i64, i64, i32, u32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.sdkde_score.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
+    lib.sdkde_debias.argtypes = [c_fp, c_fp, i64, i32, f64, c_fp, c_fp]
+    lib.sdkde_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
+    lib.sdkde_status_string.argtypes = [ctypes.c_int]
+    lib.sdkde_status_string.restype = ctypes.c_char_p
+    lib.sdkde_profile_enable.argtypes = [ctypes.c_int]
+    lib.sdkde_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
+    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval",
+                 "sdkde_profile_enable", "sdkde_profile_summary"):
+        getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def sdkde_status_string(status: int) -> str:
+    return load().sdkde_status_string(int(status)).decode()
+
+
+def _check(call: str, status: int) -> None:
+    if status != SDKDE_OK:
+        raise SdkdeError(call, status, sdkde_status_string(status))
+
+
+def _dev_f32(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous fp32 tensor on the GPU")
+    return t
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def sdkde_workspace_bytes(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) -> int:
+    out = ctypes.c_size_t(0)
+    _check("sdkde_workspace_bytes", load().sdkde_workspace_bytes(n, m, d, flags, ctypes.byref(out)))
+    return int(out.value)
+
+
+def make_workspace(n: int, m: int, d: int, device="cuda") -> torch.Tensor:
+    """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes."""
+    return torch.empty(sdkde_workspace_bytes(n, m, d), dtype=torch.uint8, device=device)
+
+
+def _workspace(ws, n, m, d, device):
+    if ws is None:
+        ws = make_workspace(n, m, d, device)
+    if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
+        raise TypeError("workspace must be a contiguous uint8 tensor on the GPU")
+    return ws
+
+
+def sdkde_score(samples, h, points=None, out=None, workspace=None, flags=SDKDE_PREC_FP32, stream=None):
+    """score_out[m,d]: empirical KDE score at `points` (None: at the samples)."""
+    x = _dev_f32(samples, "samples")
+    n, d = x.shape
+    if points is None:
+        m, p_ptr = n, None
+    else:
+        p = _dev_f32(points, "points")
+        if p.dim() != 2 or p.shape[1] != d:
+            raise ValueError("points must be [m, d]")
+        m, p_ptr = p.shape[0], p.data_ptr()
+    if out is None:
+        out = torch.empty((m, d), dtype=torch.float32, device=x.device)
+    _dev_f32(out, "out")
+    if tuple(out.shape) != (m, d):
+        raise ValueError("out must be [m, d]")
+    ws = _workspace(workspace, n, m, d, x.device)
+    _check("sdkde_score", load().sdkde_score(x.data_ptr(), n, p_ptr, m, d, float(h), out.data_ptr(),
+                                             ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
+    return out
+
+
+def sdkde_debias(samples, score, h, out=None, stream=None):
+    """samples + (h^2/2) score, elementwise."""
+    x, s = _dev_f32(samples, "samples"), _dev_f32(score, "score")
+    if x.shape != s.shape:
+        raise ValueError("samples and score differ in shape")
+    n, d = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    _dev_f32(out, "out")
+    if out.shape != x.shape:
+        raise ValueError("out must have the shape of samples")
+    _check("sdkde_debias", load().sdkde_debias(x.data_ptr(), s.data_ptr(), n, d, float(h), out.data_ptr(),
+                                               _stream_handle(stream)))
+    return out
+
+
+def sdkde_eval(samples_sd, queries, h, density_out=None, log_density_out=None, want="density",
+               workspace=None, flags=SDKDE_PREC_FP32, stream=None):
+    """KDE of samples_sd at the queries.  want: "density", "log" or "both" selects which outputs
+    are allocated when none is passed in.  Returns (density, log_density), None for the absent one."""
+    x, q = _dev_f32(samples_sd, "samples_sd"), _dev_f32(queries, "queries")
+    n, d = x.shape
+    if q.dim() != 2 or q.shape[1] != d:
+        raise ValueError("queries must be [m, d]")
+    m = q.shape[0]
+    if density_out is None and log_density_out is None:
+        if want in ("density", "both"):
+            density_out = torch.empty(m, dtype=torch.float32, device=x.device)
+        if want in ("log", "both"):
+            log_density_out = torch.empty(m, dtype=torch.float32, device=x.device)
+    for t, name in ((density_out, "density_out"), (log_density_out, "log_density_out")):
+        if t is not None:
+            _dev_f32(t, name)
+            if t.numel() != m:
+                raise ValueError(f"{name} must have m elements")
+    ws = _workspace(workspace, n, m, d, x.device)
+    _check("sdkde_eval", load().sdkde_eval(
+        x.data_ptr(), n, q.data_ptr(), m, d, float(h),
+        None if density_out is None else density_out.data_ptr(),
+        None if log_density_out is None else log_density_out.data_ptr(),
+        ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
+    return density_out, log_density_out
+
+
+def sdkde_profile_enable(on: bool) -> None:
+    _check("sdkde_profile_enable", load().sdkde_profile_enable(1 if on else 0))
+
+
+def sdkde_profile_summary(which: int):
+    """(launches, total_ms) of the main pair kernel for which = 0 (score) or 1 (eval)."""
+    count, total = ctypes.c_int(0), ctypes.c_float(0.0)
+    _check("sdkde_profile_summary", load().sdkde_profile_summary(which, ctypes.byref(count), ctypes.byref(total)))
+    return int(count.value), float(total.value)

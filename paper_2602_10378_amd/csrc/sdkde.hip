@@ -1,0 +1,759 @@
+// SD-KDE hot path for MI355X (gfx950 / CDNA4): prep, pair-interaction kernels (fp32 MFMA for
+// d >= 4, direct differences for thin d), split reduction + epilogues, and the C ABI.
+//
+// Notation follows the paper: c = 1/(2h^2), phi_ij = exp(-c |p_i - x_j|^2),
+// D_i = sum_j phi_ij, T_i = sum_j phi_ij x_j  (Method section: T = Phi X).
+//
+// All coordinates are centred on the sample mean and scaled by a = sqrt(c log2 e), so that
+// the squared distance in scaled units is directly the (negated) argument of exp2:
+//     phi_ij = exp2( 2 p~_i . x~_j - |p~_i|^2 - |x~_j|^2 ).
+// The cross term is the Gram-matrix tile of the Method section, computed with fp32 MFMA;
+// the score numerator uses Phi X with the Phi tile still in the registers the first MFMA
+// left it in.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <math.h>
+#include <type_traits>
+#include "sdkde.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;            // 4 waves per workgroup
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kTile = 16;              // MFMA 16x16x4 tile edge
+constexpr int kRowPad = 1024;          // row padding of every prepared array (>= rows per workgroup)
+constexpr float kPadNorm = -1.0e30f;   // "-|x|^2" of a padding sample: exp2 of it is exactly 0
+constexpr float kPadCoord = 1.0e18f;   // thin-d padding coordinate: squared distance ~1e36, exp2(-that) = 0
+constexpr int kMeanBlocks = 128;
+constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3, MFMA path above
+
+inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+
+// ------------------------------------------------------------------------------------------
+// Prep: column means (deterministic two-stage reduction), then centre + scale + pad.
+// ------------------------------------------------------------------------------------------
+
+// partial[b][c] = sum over this block's rows of x[row][c], double accumulation.
+__global__ __launch_bounds__(kBlock) void mean_partial_kernel(const float* __restrict__ x, int64_t n,
+                                                              int d, double* __restrict__ partial)
+{
+    __shared__ double red[kBlock];
+    const int rows_per_iter = kBlock / d;              // d <= 128 < kBlock
+    const int rr = threadIdx.x / d, c = threadIdx.x % d;
+    double acc = 0.0;
+    if (rr < rows_per_iter) {
+        for (int64_t row = (int64_t)blockIdx.x * rows_per_iter + rr; row < n;
+             row += (int64_t)gridDim.x * rows_per_iter)
+            acc += (double)x[row * d + c];
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < d) {
+        double s = 0.0;
+        for (int r = 0; r < rows_per_iter; ++r) s += red[r * d + threadIdx.x];
+        partial[(int64_t)blockIdx.x * d + threadIdx.x] = s;
+    }
+}
+
+__global__ void mean_final_kernel(const double* __restrict__ partial, int blocks, int d, int64_t n,
+                                  float* __restrict__ mean)
+{
+    int c = threadIdx.x;
+    if (c >= d) return;
+    double s = 0.0;
+    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * d + c];
+    mean[c] = (float)(s / (double)n);
+}
+
+// One thread per padded row.  Writes xs[row][dp] = a (x - mean) (0 in padding columns and rows),
+// nrm[row] = -|xs[row]|^2 (kPadNorm for padding rows) and, if xt != nullptr, the same values in
+// 16-sample blocks transposed: xt[row/16][col][row%16].
+__global__ __launch_bounds__(kBlock) void prep_mfma_kernel(const float* __restrict__ x, int64_t n, int d,
+                                                           int dp, int64_t rows_pad,
+                                                           const float* __restrict__ mean, float a,
+                                                           float* __restrict__ xs, float* __restrict__ xt,
+                                                           float* __restrict__ nrm)
+{
+    int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (row >= rows_pad) return;
+    const bool live = row < n;
+    double acc = 0.0;
+    float* xt_row = xt ? xt + (row / kTile) * (int64_t)dp * kTile + (row % kTile) : nullptr;
+    for (int c = 0; c < dp; ++c) {
+        float v = 0.0f;
+        if (live && c < d) v = a * (x[row * d + c] - mean[c]);
+        xs[row * dp + c] = v;
+        if (xt_row) xt_row[(int64_t)c * kTile] = v;
+        acc += (double)v * (double)v;
+    }
+    nrm[row] = live ? -(float)acc : kPadNorm;
+}
+
+// Thin-d variant: xs[row][d] = a (x - mean), padding rows get pad_value in every coordinate.
+__global__ __launch_bounds__(kBlock) void prep_thin_kernel(const float* __restrict__ x, int64_t n, int d,
+                                                           int64_t rows_pad, const float* __restrict__ mean,
+                                                           float a, float pad_value, float* __restrict__ xs)
+{
+    int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (row >= rows_pad) return;
+    for (int c = 0; c < d; ++c)
+        xs[row * d + c] = row < n ? a * (x[row * d + c] - mean[c]) : pad_value;
+}
+
+// ------------------------------------------------------------------------------------------
+// Main pair kernel, MFMA path.
+//
+// One wave owns NI tiles of 16 evaluation rows (kept in registers as the B operand) and
+// streams 16-sample tiles of the other set.  For every (row tile, sample tile) pair:
+//   C[j][i]  = -|p_i|^2 - |x_j|^2                        (VALU, accumulator initialisation)
+//   C       += X_J (16 x dp) * (2 P_I)^T (dp x 16)       (dp/4 MFMA 16x16x4, fp32)
+//   Phi^T    = exp2(C)                                   (v_exp_f32)
+//   D_i     += sum_j Phi^T[j][i]                         (VALU, per-lane partial)
+//   T^T     += X_J^T (dp x 16) * Phi^T (16 x 16)         (dp/4 MFMA; SCORE only)
+// The 16x16x4 accumulator layout (lane l, register v) = (row 4*(l/16)+v, column l%16) is exactly
+// the B-operand layout (k = l/16, n = l%16) of the second MFMA for the four samples
+// j = 4*(l/16)+v, so Phi never leaves its registers: register v is the B operand of the MFMA
+// whose A operand holds samples {v, 4+v, 8+v, 12+v}; the blocked-transposed copy xt supplies
+// that A operand with one float4 load per lane.  The contraction order over coordinates in the
+// first MFMA is likewise permuted (MFMA kk contracts coordinates {kk, 4+kk, 8+kk, 12+kk} of each
+// 16-column block) so that both operands are plain float4 row loads.
+//
+// SELF (score at the samples themselves): the pair (i, i) is left out of D and T and the
+// epilogue restores it analytically (phi_ii = 1), because T_i/D_i - x_i would otherwise cancel
+// against the large self term whenever a point has few neighbours.
+//
+// Grid: blockIdx.x = row_block * S + split; each workgroup handles RB = 64*NI rows and the
+// sample tiles [split*tiles_per_split, min(ntiles, (split+1)*tiles_per_split)).  With S a
+// multiple of 8 the round-robin placement of workgroups on the 8 XCDs makes each XCD stream
+// only its own eighth of the samples through its L2.
+// All arrays are padded so that every access below is in bounds:
+//   ps, pn : m_pad rows (multiple of kRowPad >= RB);  xs, xt, xn : ntiles*16 rows.
+// ------------------------------------------------------------------------------------------
+template <int KB, int NI, bool SCORE, bool SELF>
+__global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
+    const float* __restrict__ ps, const float* __restrict__ pn, const float* __restrict__ xs,
+    const float* __restrict__ xt, const float* __restrict__ xn, float* __restrict__ part_t,
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad)
+{
+    constexpr int DP = KB * 16;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int r = lane & 15, g = lane >> 4;
+    const int split = blockIdx.x % nsplit;
+    const int64_t row_block = blockIdx.x / nsplit;
+    const int64_t row0 = (row_block * kWavesPerBlock + wave) * (NI * kTile);
+
+    // B operand: 2 * p~ for NI row tiles; lane (r, g) holds coordinates 16kb + 4g .. +3 of row r.
+    f32x4 b[NI][KB];
+    float ni[NI];
+#pragma unroll
+    for (int t = 0; t < NI; ++t) {
+        const int64_t row = row0 + t * kTile + r;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(ps + row * DP + kb * 16 + g * 4);
+            b[t][kb] = v * 2.0f;
+        }
+        ni[t] = pn[row];
+    }
+
+    f32x4 tacc[NI][SCORE ? KB : 1];
+    float dacc[NI];
+#pragma unroll
+    for (int t = 0; t < NI; ++t) {
+        dacc[t] = 0.0f;
+#pragma unroll
+        for (int mb = 0; mb < (SCORE ? KB : 1); ++mb) tacc[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const int t_begin = split * tiles_per_split;
+    const int t_end = min(ntiles, t_begin + tiles_per_split);
+
+    if (t_begin < t_end) {
+        f32x4 a1[KB], a2[SCORE ? KB : 1], nj;
+        auto load_tile = [&](int jt, f32x4 (&la1)[KB], f32x4 (&la2)[SCORE ? KB : 1], f32x4& lnj) {
+            const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) la1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
+            if (SCORE) {
+                const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
+#pragma unroll
+                for (int mb = 0; mb < KB; ++mb)
+                    la2[mb] = *reinterpret_cast<const f32x4*>(trow + mb * 16 * kTile);
+            }
+            lnj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
+        };
+        load_tile(t_begin, a1, a2, nj);
+
+        // One (all NI row tiles) x (sample tile jt) step.  DIAG: sample tile jt is one of this
+        // wave's own row tiles (tile index dt0 + dt); the pair of a point with itself is left out
+        // of both sums there.
+        auto step = [&](auto diag_tag, int dt) {
+            constexpr bool DIAG = decltype(diag_tag)::value;
+#pragma unroll
+            for (int t = 0; t < NI; ++t) {
+                f32x4 c = nj + ni[t];
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].x, b[t][kb].x, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].y, b[t][kb].y, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].z, b[t][kb].z, c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].w, b[t][kb].w, c, 0, 0, 0);
+                }
+                f32x4 p;
+                p.x = __builtin_amdgcn_exp2f(c.x);
+                p.y = __builtin_amdgcn_exp2f(c.y);
+                p.z = __builtin_amdgcn_exp2f(c.z);
+                p.w = __builtin_amdgcn_exp2f(c.w);
+                if (DIAG) {
+                    // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
+                    const bool mine = t == dt;
+                    p.x = (mine && g * 4 + 0 == r) ? 0.0f : p.x;
+                    p.y = (mine && g * 4 + 1 == r) ? 0.0f : p.y;
+                    p.z = (mine && g * 4 + 2 == r) ? 0.0f : p.z;
+                    p.w = (mine && g * 4 + 3 == r) ? 0.0f : p.w;
+                }
+                dacc[t] += (p.x + p.y) + (p.z + p.w);
+                if (SCORE) {
+#pragma unroll
+                    for (int mb = 0; mb < KB; ++mb) {
+                        f32x4 acc = tacc[t][mb];
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].x, p.x, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].y, p.y, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].z, p.z, acc, 0, 0, 0);
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].w, p.w, acc, 0, 0, 0);
+                        tacc[t][mb] = acc;
+                    }
+                }
+            }
+        };
+        const int dt0 = (int)(row0 / kTile);      // tile index of this wave's first row tile
+
+        for (int jt = t_begin; jt < t_end; ++jt) {
+            f32x4 a1n[KB], a2n[SCORE ? KB : 1], njn;
+            load_tile(min(jt + 1, t_end - 1), a1n, a2n, njn);   // prefetch (clamped: always in bounds)
+
+            if (SELF && (unsigned)(jt - dt0) < (unsigned)NI)    // wave-uniform
+                step(std::true_type{}, jt - dt0);
+            else
+                step(std::false_type{}, 0);
+
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) a1[kb] = a1n[kb];
+            if (SCORE) {
+#pragma unroll
+                for (int mb = 0; mb < KB; ++mb) a2[mb] = a2n[mb];
+            }
+            nj = njn;
+        }
+    }
+
+    // Partial results of this split: T^T accumulator (lane (r, g), register v) = coordinate
+    // 16mb + 4g + v of row r; D needs the sum over the four lane groups g.
+#pragma unroll
+    for (int t = 0; t < NI; ++t) {
+        const int64_t row = row0 + t * kTile + r;
+        if (SCORE) {
+            float* dst = part_t + ((int64_t)split * m_pad + row) * DP + g * 4;
+#pragma unroll
+            for (int mb = 0; mb < KB; ++mb) *reinterpret_cast<f32x4*>(dst + mb * 16) = tacc[t][mb];
+        }
+        float dsum = dacc[t];
+        dsum += __shfl_xor(dsum, 16);
+        dsum += __shfl_xor(dsum, 32);
+        if (g == 0) part_d[(int64_t)split * m_pad + row] = dsum;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Main pair kernel, thin-d path (Appendix A: per pair one exp and a handful of ALU ops, no
+// matrix unit).  Each thread owns R evaluation rows; the streamed sample is wave-uniform, so
+// its coordinates come through scalar loads.  Accumulates D_i and, for SCORE, the direct-form
+// numerator N_i = sum_j phi_ij (x~_j - p~_i).  Same grid decomposition as the MFMA kernel with
+// row blocks of kBlock*R rows and "tiles" of 16 samples.
+// ------------------------------------------------------------------------------------------
+template <int D, int R, bool SCORE>
+__global__ __launch_bounds__(kBlock) void pair_thin_kernel(
+    const float* __restrict__ ps, const float* __restrict__ xs, float* __restrict__ part_t,
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad)
+{
+    const int split = blockIdx.x % nsplit;
+    const int64_t row_block = blockIdx.x / nsplit;
+    const int64_t row0 = row_block * (kBlock * R) + threadIdx.x;
+
+    float p[R][D], dacc[R], nacc[R][SCORE ? D : 1];
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+#pragma unroll
+        for (int k = 0; k < D; ++k) p[q][k] = ps[(row0 + (int64_t)q * kBlock) * D + k];
+        dacc[q] = 0.0f;
+#pragma unroll
+        for (int k = 0; k < (SCORE ? D : 1); ++k) nacc[q][k] = 0.0f;
+    }
+
+    const int t_begin = split * tiles_per_split;
+    const int t_end = min(ntiles, t_begin + tiles_per_split);
+    for (int jt = t_begin; jt < t_end; ++jt) {
+        const float* xj = xs + (int64_t)jt * kTile * D;    // wave-uniform address
+#pragma unroll
+        for (int jj = 0; jj < kTile; ++jj) {
+            float xv[D];
+#pragma unroll
+            for (int k = 0; k < D; ++k) xv[k] = xj[jj * D + k];
+#pragma unroll
+            for (int q = 0; q < R; ++q) {
+                float diff[D];
+                float r2 = 0.0f;
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    diff[k] = xv[k] - p[q][k];
+                    r2 = fmaf(diff[k], diff[k], r2);
+                }
+                float phi = __builtin_amdgcn_exp2f(-r2);
+                dacc[q] += phi;
+                if (SCORE) {
+#pragma unroll
+                    for (int k = 0; k < D; ++k) nacc[q][k] = fmaf(phi, diff[k], nacc[q][k]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+        const int64_t row = row0 + (int64_t)q * kBlock;
+        part_d[(int64_t)split * m_pad + row] = dacc[q];
+        if (SCORE) {
+#pragma unroll
+            for (int k = 0; k < D; ++k) part_t[((int64_t)split * m_pad + row) * D + k] = nacc[q][k];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Split reduction + epilogues (fixed summation order over splits: deterministic).
+// ------------------------------------------------------------------------------------------
+
+// mode 0 (MFMA path, separate points): score = (T/D - p~) * inv_ah2            (T = Phi X regrouping)
+// mode 1 (thin path):                   score = (N/D) * inv_ah2                (direct-form numerator)
+// mode 2 (MFMA path, at the samples):   score = (T' - p~ D') / (D' + 1) * inv_ah2
+//        where T', D' exclude the pair (i, i), whose weight is exactly 1.
+// inv_ah2 = 1 / (a h^2) undoes the coordinate scaling.  D == 0 gives 0.
+__global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
+    const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
+    int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, float inv_ah2,
+    float* __restrict__ score)
+{
+    int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= m * d) return;
+    const int64_t i = idx / d;
+    const int c = (int)(idx % d);
+    float tsum = 0.0f, dsum = 0.0f;
+    for (int s = 0; s < nsplit; ++s) {
+        tsum += part_t[((int64_t)s * m_pad + i) * dp + c];
+        dsum += part_d[(int64_t)s * m_pad + i];
+    }
+    float out = 0.0f;
+    if (mode == 2) {
+        out = fmaf(-ps[i * dp + c], dsum, tsum) / (dsum + 1.0f) * inv_ah2;
+    } else if (dsum > 0.0f) {
+        float ratio = tsum / dsum;
+        out = (mode == 1 ? ratio : ratio - ps[i * dp + c]) * inv_ah2;
+    }
+    score[idx] = out;
+}
+
+// log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
+__global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __restrict__ part_d, int nsplit,
+                                                               int64_t m, int64_t m_pad, double lognorm,
+                                                               float* __restrict__ density,
+                                                               float* __restrict__ log_density)
+{
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= m) return;
+    float dsum = 0.0f;
+    for (int s = 0; s < nsplit; ++s) dsum += part_d[(int64_t)s * m_pad + i];
+    double lp = log((double)dsum) + lognorm;      // -inf when dsum == 0
+    if (log_density) log_density[i] = (float)lp;
+    if (density) density[i] = (float)exp(lp);
+}
+
+__global__ __launch_bounds__(kBlock) void debias_kernel(const float* __restrict__ x, const float* __restrict__ s,
+                                                        int64_t total, float half_h2, float* __restrict__ out)
+{
+    int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx < total) out[idx] = fmaf(half_h2, s[idx], x[idx]);
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side: plan, workspace layout, dispatch.
+// ------------------------------------------------------------------------------------------
+
+struct Plan {
+    bool thin;
+    int d, dp;            // true and padded dimension (thin: dp == d)
+    int ni;               // MFMA: row tiles per wave; thin: rows per thread
+    int rows_per_block;
+    int64_t n_pad, m_pad; // padded sample / point row counts
+    int ntiles;           // 16-sample tiles
+    int nsplit, tiles_per_split;
+    int64_t row_blocks;
+};
+
+int env_int(const char* name, int fallback)
+{
+    const char* v = getenv(name);
+    if (!v || !*v) return fallback;
+    return atoi(v);
+}
+
+// Workgroups needed to keep 256 CUs busy with a few waves per SIMD.
+constexpr int64_t kTargetBlocks = 2048;
+
+Plan make_plan(int64_t n, int64_t m, int d, bool score)
+{
+    Plan p{};
+    p.d = d;
+    p.thin = d <= kThinMaxD;
+    p.dp = p.thin ? d : (int)round_up(d, 16);
+    p.n_pad = round_up(n, kRowPad);
+    p.m_pad = round_up(m > 0 ? m : 1, kRowPad);
+    p.ntiles = (int)((n + kTile - 1) / kTile);
+    const int max_split = p.ntiles >= 32 ? p.ntiles / 16 : 1;   // at least 16 tiles per split
+
+    // Candidate row-tile counts, largest (most operand reuse) first; a smaller one is taken
+    // only when the grid would otherwise leave most of the chip idle.
+    int cand[5];
+    int nc = 0;
+    if (p.thin) {
+        cand[nc++] = 4; cand[nc++] = 2; cand[nc++] = 1;
+    } else {
+        const int kb = p.dp / 16;
+        const int top = score ? (kb == 1 ? 8 : kb == 2 ? 4 : kb <= 4 ? 2 : 1)
+                              : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+        for (int v = top; v >= 1; v /= 2) cand[nc++] = v;
+    }
+    const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
+    const int forced_split = env_int(score ? "SDKDE_SCORE_SPLIT" : "SDKDE_EVAL_SPLIT", 0);
+    for (int q = 0; q < nc; ++q)
+        if (cand[q] == forced_ni) { cand[0] = forced_ni; nc = 1; }
+
+    for (int k = 0; k < nc; ++k) {
+        p.ni = cand[k];
+        p.rows_per_block = p.thin ? kBlock * p.ni : kWavesPerBlock * kTile * p.ni;
+        p.row_blocks = (m + p.rows_per_block - 1) / p.rows_per_block;
+        if (p.row_blocks < 1) p.row_blocks = 1;
+        int64_t want = (kTargetBlocks + p.row_blocks - 1) / p.row_blocks;
+        if (max_split >= 8) {                       // one group of splits per XCD
+            want = round_up(want < 8 ? 8 : want, 8);
+            if (want > max_split) want = max_split / 8 * 8;
+        } else if (want > max_split) {
+            want = max_split;
+        }
+        p.nsplit = (int)want;
+        if (forced_split > 0) p.nsplit = forced_split > p.ntiles ? p.ntiles : forced_split;
+        if (p.row_blocks * p.nsplit >= kTargetBlocks / 2) break;
+    }
+    p.tiles_per_split = (p.ntiles + p.nsplit - 1) / p.nsplit;
+    return p;
+}
+
+struct Workspace {
+    double* mean_partial;
+    float* mean;
+    float* xs;  float* xt;  float* xn;     // samples: scaled rows, blocked transpose, -|x|^2
+    float* ps;  float* pn;                 // evaluation points (alias xs/xn when they are the samples)
+    float* part_t;  float* part_d;
+    size_t bytes;
+};
+
+// Lays out the workspace for `plan`; base may be null (size query).  separate_points: the
+// evaluation points are an array of their own (eval, or score at points != samples).
+Workspace layout(const Plan& p, bool score, bool separate_points, void* base)
+{
+    Workspace w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = off;
+        off += (bytes + 255) / 256 * 256;
+        return base ? (char*)base + at : (char*)nullptr;
+    };
+    w.mean_partial = (double*)take(sizeof(double) * kMeanBlocks * SDKDE_MAX_D);
+    w.mean = (float*)take(sizeof(float) * (SDKDE_MAX_D + 16));
+    w.xs = (float*)take(sizeof(float) * p.n_pad * p.dp);
+    w.xt = (score && !p.thin) ? (float*)take(sizeof(float) * p.n_pad * p.dp) : nullptr;
+    w.xn = (float*)take(sizeof(float) * p.n_pad);
+    if (separate_points) {
+        w.ps = (float*)take(sizeof(float) * p.m_pad * p.dp);
+        w.pn = (float*)take(sizeof(float) * p.m_pad);
+    } else {
+        w.ps = w.xs;
+        w.pn = w.xn;
+    }
+    w.part_t = score ? (float*)take(sizeof(float) * (size_t)p.nsplit * p.m_pad * p.dp) : nullptr;
+    w.part_d = (float*)take(sizeof(float) * (size_t)p.nsplit * p.m_pad);
+    w.bytes = off;
+    return w;
+}
+
+bool bad_bandwidth(double h) { return !(h > 0.0) || !isfinite(h); }
+
+// Optional instrumentation: event pairs around the main pair kernel of each call.
+constexpr int kProfileSlots = 256;
+struct Profile {
+    bool enabled = false;
+    hipEvent_t ev[2][kProfileSlots][2] = {};   // [score|eval][launch][begin|end], created lazily
+    int count[2] = {0, 0};
+} g_profile;
+
+#define SDKDE_HIP(call)                                   \
+    do {                                                  \
+        if ((call) != hipSuccess) return SDKDE_EDEVICE;   \
+    } while (0)
+
+template <bool SCORE, bool SELF>
+int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
+{
+    const dim3 grid((unsigned)(p.row_blocks * p.nsplit)), block(kBlock);
+    if ((int64_t)p.row_blocks * p.nsplit > 0x7fffffffLL) return SDKDE_EUNSUPPORTED;
+    // Host-side shape check: every row the grid touches exists in the padded arrays.
+    if (p.row_blocks * p.rows_per_block > p.m_pad || (int64_t)p.ntiles * kTile > p.n_pad) return SDKDE_EINVAL;
+
+#define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                   \
+    hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, SCORE, SELF>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt, \
+                       w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad)
+#define SDKDE_LAUNCH_THIN(D_, R_)                                                                  \
+    hipLaunchKernelGGL((pair_thin_kernel<D_, R_, SCORE>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
+                       w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad)
+#define SDKDE_CASE_NI(KB_, NI_) \
+    case NI_: SDKDE_LAUNCH_MFMA(KB_, NI_); break;
+
+    if (p.thin) {
+        const int key = p.d * 10 + p.ni;
+        switch (key) {
+            case 14: SDKDE_LAUNCH_THIN(1, 4); break;
+            case 12: SDKDE_LAUNCH_THIN(1, 2); break;
+            case 11: SDKDE_LAUNCH_THIN(1, 1); break;
+            case 24: SDKDE_LAUNCH_THIN(2, 4); break;
+            case 22: SDKDE_LAUNCH_THIN(2, 2); break;
+            case 21: SDKDE_LAUNCH_THIN(2, 1); break;
+            case 34: SDKDE_LAUNCH_THIN(3, 4); break;
+            case 32: SDKDE_LAUNCH_THIN(3, 2); break;
+            case 31: SDKDE_LAUNCH_THIN(3, 1); break;
+            default: return SDKDE_EUNSUPPORTED;
+        }
+    } else {
+        const int kb = p.dp / 16;
+        switch (kb) {
+            case 1:
+                switch (p.ni) { SDKDE_CASE_NI(1, 16) SDKDE_CASE_NI(1, 8) SDKDE_CASE_NI(1, 4) SDKDE_CASE_NI(1, 2) SDKDE_CASE_NI(1, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 2:
+                switch (p.ni) { SDKDE_CASE_NI(2, 8) SDKDE_CASE_NI(2, 4) SDKDE_CASE_NI(2, 2) SDKDE_CASE_NI(2, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 3:
+                switch (p.ni) { SDKDE_CASE_NI(3, 4) SDKDE_CASE_NI(3, 2) SDKDE_CASE_NI(3, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 4:
+                switch (p.ni) { SDKDE_CASE_NI(4, 4) SDKDE_CASE_NI(4, 2) SDKDE_CASE_NI(4, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 5:
+                switch (p.ni) { SDKDE_CASE_NI(5, 2) SDKDE_CASE_NI(5, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 6:
+                switch (p.ni) { SDKDE_CASE_NI(6, 2) SDKDE_CASE_NI(6, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 7:
+                switch (p.ni) { SDKDE_CASE_NI(7, 2) SDKDE_CASE_NI(7, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            case 8:
+                switch (p.ni) { SDKDE_CASE_NI(8, 2) SDKDE_CASE_NI(8, 1) default: return SDKDE_EUNSUPPORTED; }
+                break;
+            default: return SDKDE_EUNSUPPORTED;
+        }
+    }
+#undef SDKDE_CASE_NI
+#undef SDKDE_LAUNCH_THIN
+#undef SDKDE_LAUNCH_MFMA
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
+// Column means of src[rows][d] into w.mean.
+int launch_mean(const float* src, int64_t rows, int d, const Workspace& w, hipStream_t st)
+{
+    hipLaunchKernelGGL(mean_partial_kernel, dim3(kMeanBlocks), dim3(kBlock), 0, st, src, rows, d, w.mean_partial);
+    hipLaunchKernelGGL(mean_final_kernel, dim3(1), dim3(SDKDE_MAX_D), 0, st, w.mean_partial, kMeanBlocks, d, rows,
+                       w.mean);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
+// Centre/scale/pad `src` into (dst, dst_t, dst_n) with rows_pad rows.
+int launch_prep(const Plan& p, const float* src, int64_t rows, int64_t rows_pad, float a, const Workspace& w,
+                float* dst, float* dst_t, float* dst_n, float pad_value, hipStream_t st)
+{
+    const dim3 grid((unsigned)((rows_pad + kBlock - 1) / kBlock)), block(kBlock);
+    if (p.thin)
+        hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, src, rows, p.d, rows_pad, w.mean, a, pad_value, dst);
+    else
+        hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, src, rows, p.d, p.dp, rows_pad, w.mean, a, dst,
+                           dst_t, dst_n);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
+int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h, uint32_t flags)
+{
+    if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
+    if (d > SDKDE_MAX_D || flags != SDKDE_PREC_FP32) return SDKDE_EUNSUPPORTED;
+    if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
+    return SDKDE_OK;
+}
+
+// edge 0: before the main kernel of a call of kind `which`; edge 1: after it.
+int profile_mark(int which, int edge, hipStream_t st)
+{
+    if (!g_profile.enabled || g_profile.count[which] >= kProfileSlots) return SDKDE_OK;
+    hipEvent_t& e = g_profile.ev[which][g_profile.count[which]][edge];
+    if (!e) SDKDE_HIP(hipEventCreate(&e));
+    SDKDE_HIP(hipEventRecord(e, st));
+    if (edge == 1) ++g_profile.count[which];
+    return SDKDE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_t* bytes)
+{
+    if (!bytes) return SDKDE_EINVAL;
+    int rc = check_common(bytes, n, m, d, 1.0, flags);
+    if (rc != SDKDE_OK) return rc;
+    // Largest of: score at the samples themselves, score at m separate points, eval at m queries.
+    size_t need = layout(make_plan(n, n, d, true), true, false, nullptr).bytes;
+    if (m > 0) {
+        size_t b = layout(make_plan(n, m, d, true), true, true, nullptr).bytes;
+        need = b > need ? b : need;
+        b = layout(make_plan(n, m, d, false), false, true, nullptr).bytes;
+        need = b > need ? b : need;
+    }
+    *bytes = need;
+    return SDKDE_OK;
+}
+
+int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m, int32_t d, double h,
+                float* score_out, void* workspace, size_t workspace_bytes, uint32_t flags, void* stream)
+{
+    int rc = check_common(samples, n, m, d, h, flags);
+    if (rc != SDKDE_OK) return rc;
+    const bool self = points == nullptr || (points == samples && m == n);
+    if (points == nullptr && m != n) return SDKDE_EINVAL;
+    if (m == 0) return SDKDE_OK;
+    if (!score_out) return SDKDE_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+
+    const Plan p = make_plan(n, m, d, true);
+    const Workspace w = layout(p, true, !self, workspace);
+    if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));   // sqrt(c log2 e)
+    // When the points are the samples (m == n, so m_pad == n_pad), one prepared array serves
+    // as both operands.
+    if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, w.xt, w.xn, kPadCoord, st)) != SDKDE_OK) return rc;
+    if (!self &&
+        (rc = launch_prep(p, points, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, st)) != SDKDE_OK)
+        return rc;
+
+    if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
+    rc = self ? launch_pair<true, true>(p, w, st) : launch_pair<true, false>(p, w, st);
+    if (rc != SDKDE_OK) return rc;
+    if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
+
+    const int64_t total = m * (int64_t)d;
+    const float inv_ah2 = (float)(1.0 / (a * h * h));
+    hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+                       w.part_t, w.part_d, w.ps, p.nsplit, m, p.m_pad, d, p.dp, p.thin ? 1 : (self ? 2 : 0), inv_ah2, score_out);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
+int sdkde_debias(const float* samples, const float* score, int64_t n, int32_t d, double h, float* samples_sd_out,
+                 void* stream)
+{
+    if (!samples || !score || !samples_sd_out || n < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
+    const int64_t total = n * (int64_t)d;
+    if (total == 0) return SDKDE_OK;
+    hipLaunchKernelGGL(debias_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                       (hipStream_t)stream, samples, score, total, (float)(0.5 * h * h), samples_sd_out);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
+int sdkde_eval(const float* samples_sd, int64_t n, const float* queries, int64_t m, int32_t d, double h,
+               float* density_out, float* log_density_out, void* workspace, size_t workspace_bytes, uint32_t flags,
+               void* stream)
+{
+    int rc = check_common(samples_sd, n, m, d, h, flags);
+    if (rc != SDKDE_OK) return rc;
+    if (m == 0) return SDKDE_OK;
+    if (!queries || (!density_out && !log_density_out)) return SDKDE_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+
+    const Plan p = make_plan(n, m, d, false);
+    const Workspace w = layout(p, false, true, workspace);
+    if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
+    if ((rc = launch_mean(samples_sd, n, d, w, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_prep(p, samples_sd, n, p.n_pad, (float)a, w, w.xs, nullptr, w.xn, kPadCoord, st)) != SDKDE_OK)
+        return rc;
+    if ((rc = launch_prep(p, queries, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, st)) != SDKDE_OK) return rc;
+
+    if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_pair<false, false>(p, w, st)) != SDKDE_OK) return rc;
+    if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
+
+    const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
+    hipLaunchKernelGGL(eval_epilogue_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
+                       p.nsplit, m, p.m_pad, lognorm, density_out, log_density_out);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
+const char* sdkde_status_string(int status)
+{
+    switch (status) {
+        case SDKDE_OK: return "ok";
+        case SDKDE_EINVAL: return "invalid argument";
+        case SDKDE_EUNSUPPORTED: return "unsupported dimension, size or flag";
+        case SDKDE_EWORKSPACE: return "workspace missing, misaligned or too small";
+        case SDKDE_EDEVICE: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int sdkde_profile_enable(int on)
+{
+    g_profile.enabled = on != 0;
+    g_profile.count[0] = g_profile.count[1] = 0;
+    return SDKDE_OK;
+}
+
+int sdkde_profile_summary(int which, int* launches, float* total_ms)
+{
+    if (which < 0 || which > 1 || !launches || !total_ms) return SDKDE_EINVAL;
+    float total = 0.0f;
+    for (int k = 0; k < g_profile.count[which]; ++k) {
+        float ms = 0.0f;
+        SDKDE_HIP(hipEventSynchronize(g_profile.ev[which][k][1]));
+        SDKDE_HIP(hipEventElapsedTime(&ms, g_profile.ev[which][k][0], g_profile.ev[which][k][1]));
+        total += ms;
+    }
+    *launches = g_profile.count[which];
+    *total_ms = total;
+    return SDKDE_OK;
+}
+
+}  // extern "C"

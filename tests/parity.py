@@ -1,0 +1,63 @@
+"""Comparison helpers for GPU-vs-oracle parity (no estimator arithmetic here).
+
+Tolerances (from the benchmark spec: max relative error <= 1e-3 on density, <= 1e-3 * |s| on
+score for the fp32-accumulate path):
+  score   : per point, |s_gpu - s_ref|_2 <= 1e-3 * max(|s_ref|_2, 1e-3 * rms_i |s_ref,i|_2)
+  density : |p_gpu - p_ref| <= 1e-3 * p_ref wherever p_ref >= 1e-30 (fp32-representable with margin)
+  log dens: |log p_gpu - log p_ref| <= 1e-3 (used where the density itself is below fp32 range)
+"""
+import numpy as np
+
+TOL = 1e-3
+
+
+def score_error(s_gpu, s_ref):
+    """Largest per-point error relative to its allowance (<= 1 passes) and the global relative
+    Frobenius error."""
+    s_gpu = np.asarray(s_gpu, dtype=np.float64)
+    s_ref = np.asarray(s_ref, dtype=np.float64)
+    err = np.linalg.norm(s_gpu - s_ref, axis=1)
+    ref = np.linalg.norm(s_ref, axis=1)
+    rms = float(np.sqrt(np.mean(ref**2))) if len(ref) else 0.0
+    allow = TOL * np.maximum(ref, 1e-3 * rms)
+    allow = np.where(allow > 0, allow, np.finfo(np.float64).tiny)
+    frob = float(np.linalg.norm(s_gpu - s_ref) / max(np.linalg.norm(s_ref), 1e-300))
+    return float(np.max(err / allow)) if len(err) else 0.0, frob
+
+
+def assert_score_close(s_gpu, s_ref, what=""):
+    assert np.all(np.isfinite(s_gpu)), f"{what}: non-finite score"
+    worst, frob = score_error(s_gpu, s_ref)
+    assert worst <= 1.0, f"{what}: score error {worst:.3g}x the allowance (global rel {frob:.3g})"
+    return worst, frob
+
+
+def assert_density_close(p_gpu, logp_ref, what=""):
+    p_gpu = np.asarray(p_gpu, dtype=np.float64)
+    p_ref = np.exp(logp_ref)
+    big = p_ref >= 1e-30
+    rel = np.abs(p_gpu[big] - p_ref[big]) / p_ref[big]
+    worst = float(rel.max()) if rel.size else 0.0
+    assert worst <= TOL, f"{what}: density rel error {worst:.3g}"
+    return worst
+
+
+def assert_log_density_close(lp_gpu, logp_ref, what=""):
+    lp_gpu = np.asarray(lp_gpu, dtype=np.float64)
+    assert np.all(np.isfinite(lp_gpu)), f"{what}: non-finite log density"
+    worst = float(np.max(np.abs(lp_gpu - logp_ref))) if lp_gpu.size else 0.0
+    assert worst <= TOL, f"{what}: log-density abs error {worst:.3g}"
+    return worst
+
+
+def assert_shifted_close(x_sd_gpu, x_sd_ref, s_ref, h, what=""):
+    """Shifted samples: the shift (h^2/2) s carries the score tolerance; on top of it the fp32
+    result cannot resolve less than one rounding (2^-24 relative) of x_sd itself."""
+    x_sd_gpu = np.asarray(x_sd_gpu, dtype=np.float64)
+    ref = np.linalg.norm(s_ref, axis=1)
+    rms = float(np.sqrt(np.mean(ref**2)))
+    allow = 0.5 * h * h * TOL * np.maximum(ref, 1e-3 * rms) + 2.0**-24 * np.linalg.norm(x_sd_ref, axis=1)
+    err = np.linalg.norm(x_sd_gpu - x_sd_ref, axis=1)
+    worst = float(np.max(err / allow))
+    assert worst <= 1.0, f"{what}: shifted-sample error {worst:.3g}x the allowance"
+    return worst

@@ -1,0 +1,184 @@
+"""GPU parity: the HIP library, called through its C ABI (ctypes binding), against the CPU
+oracle on the same seeded inputs, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+import sdkde_inputs
+from parity import assert_density_close, assert_log_density_close, assert_score_close, assert_shifted_close
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    return P, torch
+
+
+def _gpu_pipeline(P, torch, x, q, h):
+    xd = torch.from_numpy(x).cuda()
+    qd = torch.from_numpy(q).cuda()
+    ws = P.make_workspace(x.shape[0], q.shape[0], x.shape[1])
+    s = P.sdkde_score(xd, h, workspace=ws)
+    x_sd = P.sdkde_debias(xd, s, h)
+    dens, logd = P.sdkde_eval(x_sd, qd, h, want="both", workspace=ws)
+    torch.cuda.synchronize()
+    return s.cpu().numpy(), x_sd.cpu().numpy(), dens.cpu().numpy(), logd.cpu().numpy()
+
+
+def _mixture(n, m, d, seed):
+    if d == 1:
+        return sdkde_inputs.mixture_1d(n, m, seed)
+    return sdkde_inputs.gaussian_mixture(n, m, d, components=4, seed=seed, diag_cov=(d >= 64))
+
+
+# sizes: several 16-sample tiles and row blocks plus ragged tails; d covers the thin path
+# (1-3), the MFMA path with zero-padded columns (5, 20, 33, 100) and exact multiples of 16.
+CASES = [
+    (4096, 1024, 16, 0),     # config C1
+    (1000, 333, 16, 1),
+    (2049, 17, 16, 2),
+    (3000, 777, 1, 0),
+    (1500, 300, 2, 3),
+    (1500, 300, 3, 4),
+    (1200, 200, 4, 5),
+    (1200, 200, 5, 6),
+    (1100, 130, 20, 7),
+    (1100, 130, 32, 8),
+    (900, 100, 33, 9),
+    (2048, 512, 64, 10),
+    (700, 90, 100, 11),
+    (700, 90, 128, 12),
+]
+
+
+@pytest.mark.parametrize("n,m,d,seed", CASES)
+def test_pipeline_matches_oracle(lib, n, m, d, seed):
+    P, torch = lib
+    print(f"case n={n} m={m} d={d} seed={seed}", flush=True)
+    x, q, h = _mixture(n, m, d, seed)
+    s, x_sd, dens, logd = _gpu_pipeline(P, torch, x, q, h)
+    s_ref, x_sd_ref, logp_ref = oracle.sd_kde_log_density(x, q, h)
+    what = f"n={n} m={m} d={d}"
+    assert_score_close(s, s_ref, what)
+    assert_shifted_close(x_sd, x_sd_ref, s_ref, h, what)
+    assert_log_density_close(logd, logp_ref, what)
+    assert_density_close(dens, logp_ref, what)
+    # stage-wise: eval alone on the oracle's shifted samples (rounded to fp32)
+    x_sd32 = x_sd_ref.astype(np.float32)
+    _, logd2 = P.sdkde_eval(torch.from_numpy(x_sd32).cuda(), torch.from_numpy(q).cuda(), h, want="log")
+    assert_log_density_close(logd2.cpu().numpy(), oracle.eval_log_density(x_sd32, q, h), what + " eval-only")
+
+
+@pytest.mark.parametrize("n,d", [(1, 16), (1, 1), (2, 16), (15, 16), (16, 16), (17, 5), (63, 2), (65, 64)])
+def test_tiny_sample_sets(lib, n, d):
+    P, torch = lib
+    print(f"tiny n={n} d={d}", flush=True)
+    rng = np.random.default_rng(100 + n + d)
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    q = rng.standard_normal((9, d)).astype(np.float32)
+    h = 0.8
+    s, x_sd, dens, logd = _gpu_pipeline(P, torch, x, q, h)
+    s_ref, _, logp_ref = oracle.sd_kde_log_density(x, q, h)
+    if n == 1:
+        assert np.all(s == 0.0)
+    assert_score_close(s, s_ref, f"n={n} d={d}")
+    assert_log_density_close(logd, logp_ref, f"n={n} d={d}")
+    assert_density_close(dens, logp_ref, f"n={n} d={d}")
+
+
+@pytest.mark.parametrize("d", [1, 3, 16, 40])
+def test_score_at_separate_points(lib, d):
+    P, torch = lib
+    print(f"separate points d={d}", flush=True)
+    x, q, h = _mixture(1300, 257, d, 21)
+    got = P.sdkde_score(torch.from_numpy(x).cuda(), h, points=torch.from_numpy(q).cuda()).cpu().numpy()
+    assert_score_close(got, oracle.score(x, h, points=q), f"points d={d}")
+
+
+def test_single_sample_closed_form(lib):
+    # n = 1: s(p) = -(p - x1)/h^2 exactly as in the paper's score formula.
+    P, torch = lib
+    x1 = np.array([[0.5, -1.0, 2.0, 0.25] * 4], dtype=np.float32)
+    p = np.random.default_rng(3).standard_normal((50, 16)).astype(np.float32)
+    h = 1.3
+    got = P.sdkde_score(torch.from_numpy(x1).cuda(), h, points=torch.from_numpy(p).cuda()).cpu().numpy()
+    assert_score_close(got, -(p.astype(np.float64) - x1) / h**2, "n=1")
+
+
+def test_identical_samples_have_zero_score(lib):
+    P, torch = lib
+    x = np.tile(np.linspace(-1, 1, 16, dtype=np.float32), (200, 1))
+    s = P.sdkde_score(torch.from_numpy(x).cuda(), 0.7).cpu().numpy()
+    assert np.max(np.abs(s)) < 1e-5
+
+
+@pytest.mark.parametrize("d", [1, 16])
+def test_translation_far_from_origin(lib, d):
+    # The library centres on the sample mean, so a large common offset must not cost accuracy
+    # beyond the rounding of the shifted fp32 inputs themselves.
+    P, torch = lib
+    x, q, h = _mixture(2000, 200, d, 31)
+    off = np.float32(1000.0)
+    xo, qo = (x + off).astype(np.float32), (q + off).astype(np.float32)
+    s, _, _, logd = _gpu_pipeline(P, torch, xo, qo, h)
+    s_ref, _, logp_ref = oracle.sd_kde_log_density(xo, qo, h)
+    assert_score_close(s, s_ref, f"offset d={d}")
+    assert_log_density_close(logd, logp_ref, f"offset d={d}")
+
+
+@pytest.mark.parametrize("d", [1, 16, 64])
+def test_bitwise_deterministic(lib, d):
+    P, torch = lib
+    x, q, h = _mixture(3000, 500, d, 41)
+    a = _gpu_pipeline(P, torch, x, q, h)
+    b = _gpu_pipeline(P, torch, x, q, h)
+    for u, v in zip(a, b):
+        assert np.array_equal(u, v)
+
+
+def test_permutation_of_samples(lib):
+    P, torch = lib
+    x, q, h = _mixture(2500, 300, 16, 51)
+    perm = np.random.default_rng(0).permutation(len(x))
+    s1, _, _, l1 = _gpu_pipeline(P, torch, x, q, h)
+    s2, _, _, l2 = _gpu_pipeline(P, torch, np.ascontiguousarray(x[perm]), q, h)
+    assert_score_close(s2, s1[perm].astype(np.float64), "perm")
+    assert np.max(np.abs(l1 - l2)) < 1e-4
+
+
+def test_far_query_and_far_point(lib):
+    # every phi underflows in fp32: documented behaviour is log density -inf, density 0, score 0
+    P, torch = lib
+    x, _, h = _mixture(500, 1, 16, 61)
+    far = (x.mean(0, keepdims=True) + 1e3).astype(np.float32)
+    xd, fd = torch.from_numpy(x).cuda(), torch.from_numpy(far).cuda()
+    dens, logd = P.sdkde_eval(xd, fd, h, want="both")
+    assert dens.item() == 0.0 and logd.item() == float("-inf")
+    assert np.all(P.sdkde_score(xd, h, points=fd).cpu().numpy() == 0.0)
+
+
+def test_argument_errors(lib):
+    P, torch = lib
+    x = torch.zeros((64, 16), device="cuda")
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_score(x, 0.0)
+    assert e.value.status == 1
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_score(x, float("nan"))
+    assert e.value.status == 1
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_score(x, 1.0, workspace=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    assert e.value.status == 3
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_score(torch.zeros((8, 200), device="cuda"), 1.0)
+    assert e.value.status == 2
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_eval(x, torch.zeros((4, 16), device="cuda"), -1.0)
+    assert e.value.status == 1
+    # empty query set is a no-op
+    dens, _ = P.sdkde_eval(x, torch.zeros((0, 16), device="cuda"), 1.0)
+    assert dens.numel() == 0
