@@ -14,6 +14,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 VALU forms are kept off
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form",     # MFMA accumulators in VGPRs: no AGPR copies around VALU work
     "-Wno-unused-command-line-argument",
 ]
 

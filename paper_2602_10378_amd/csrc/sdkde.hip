@@ -139,7 +139,10 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const float* __restrict__ xt, const float* __restrict__ xn, float* __restrict__ part_t,
     float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad)
 {
+    static_assert(NI >= 2 && NI % 2 == 0, "the software pipeline alternates two accumulator sets");
     constexpr int DP = KB * 16;
+    constexpr int NM = 4 * KB;                 // MFMAs per contraction and tile
+    constexpr int KT = SCORE ? KB : 1;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int r = lane & 15, g = lane >> 4;
@@ -161,21 +164,22 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         ni[t] = pn[row];
     }
 
-    f32x4 tacc[NI][SCORE ? KB : 1];
+    f32x4 tacc[NI][KT];
     float dacc[NI];
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
         dacc[t] = 0.0f;
 #pragma unroll
-        for (int mb = 0; mb < (SCORE ? KB : 1); ++mb) tacc[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int mb = 0; mb < KT; ++mb) tacc[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     const int t_begin = split * tiles_per_split;
     const int t_end = min(ntiles, t_begin + tiles_per_split);
 
     if (t_begin < t_end) {
-        f32x4 a1[KB], a2[SCORE ? KB : 1], nj;
-        auto load_tile = [&](int jt, f32x4 (&la1)[KB], f32x4 (&la2)[SCORE ? KB : 1], f32x4& lnj) {
+        f32x4 a1[KB], a2[KT], nj;          // operands of the current sample tile
+        f32x4 a1n[KB], a2n[KT], njn;       // ... of the next one (prefetched)
+        auto load_tile = [&](int jt, f32x4 (&la1)[KB], f32x4 (&la2)[KT], f32x4& lnj) {
             const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) la1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
@@ -187,69 +191,90 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
             }
             lnj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
         };
-        load_tile(t_begin, a1, a2, nj);
 
-        // One (all NI row tiles) x (sample tile jt) step.  DIAG: sample tile jt is one of this
-        // wave's own row tiles (tile index dt0 + dt); the pair of a point with itself is left out
-        // of both sums there.
-        auto step = [&](auto diag_tag, int dt) {
+        // Software pipeline over the flattened sequence of (sample tile, row tile) pairs u:
+        //   [first contraction of pair u+1]  (4*KB MFMAs, back to back)
+        //   [VALU clump: exp2 + row sum of pair u, accumulator init of pair u+2]
+        //   [second contraction of pair u]   (4*KB MFMAs, back to back)
+        // On gfx950 the fp32 MFMA does not overlap with VALU work of the same SIMD (measured:
+        // every VALU instruction adds its full issue time, plus ~8 clocks each time the stream
+        // switches between MFMA and VALU), so VALU work is gathered into one clump per pair
+        // instead of being interleaved, and each clump only touches results that are at least
+        // one MFMA group old, so it never waits.  creg[u & 1] holds the exponent tile of pair u,
+        // ph[u & 1] its Phi^T tile.  Scheduling barriers pin the three groups.
+        f32x4 creg[2], ph[2];
+        load_tile(t_begin, a1, a2, nj);
+        creg[0] = nj + ni[0];
+#pragma unroll
+        for (int i = 0; i < NM; ++i)
+            creg[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i / 4][i % 4], b[0][i / 4][i % 4], creg[0], 0, 0, 0);
+        creg[1] = nj + ni[1];
+
+        // One sample tile against all NI row tiles.  DIAG: the sample tile is this wave's own row
+        // tile number dt; the pair of a point with itself is left out of both sums there.
+        auto iteration = [&](auto diag_tag, int dt) {
             constexpr bool DIAG = decltype(diag_tag)::value;
 #pragma unroll
             for (int t = 0; t < NI; ++t) {
-                f32x4 c = nj + ni[t];
+                const int cur = t & 1, nxt = cur ^ 1;
+                const bool wrap1 = t + 1 >= NI, wrap2 = t + 2 >= NI;     // compile-time after unrolling
+                f32x4& c = creg[cur];
+                f32x4& phi = ph[cur];
+                const float nin = ni[(t + 2) % NI];
+                const f32x4& njx = wrap2 ? njn : nj;
+                const bool mine = DIAG && t == dt;
+
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) {
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].x, b[t][kb].x, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].y, b[t][kb].y, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].z, b[t][kb].z, c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb].w, b[t][kb].w, c, 0, 0, 0);
+                for (int i = 0; i < NM; ++i) {
+                    const int kb = i / 4, kk = i % 4;
+                    const float av = wrap1 ? a1n[kb][kk] : a1[kb][kk];
+                    creg[nxt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b[(t + 1) % NI][kb][kk], creg[nxt], 0, 0, 0);
                 }
-                f32x4 p;
-                p.x = __builtin_amdgcn_exp2f(c.x);
-                p.y = __builtin_amdgcn_exp2f(c.y);
-                p.z = __builtin_amdgcn_exp2f(c.z);
-                p.w = __builtin_amdgcn_exp2f(c.w);
+                __builtin_amdgcn_sched_barrier(0);
+
+                phi.x = __builtin_amdgcn_exp2f(c.x);
+                phi.y = __builtin_amdgcn_exp2f(c.y);
+                phi.z = __builtin_amdgcn_exp2f(c.z);
+                phi.w = __builtin_amdgcn_exp2f(c.w);
                 if (DIAG) {
                     // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
-                    const bool mine = t == dt;
-                    p.x = (mine && g * 4 + 0 == r) ? 0.0f : p.x;
-                    p.y = (mine && g * 4 + 1 == r) ? 0.0f : p.y;
-                    p.z = (mine && g * 4 + 2 == r) ? 0.0f : p.z;
-                    p.w = (mine && g * 4 + 3 == r) ? 0.0f : p.w;
+                    phi.x = (mine && g * 4 + 0 == r) ? 0.0f : phi.x;
+                    phi.y = (mine && g * 4 + 1 == r) ? 0.0f : phi.y;
+                    phi.z = (mine && g * 4 + 2 == r) ? 0.0f : phi.z;
+                    phi.w = (mine && g * 4 + 3 == r) ? 0.0f : phi.w;
                 }
-                dacc[t] += (p.x + p.y) + (p.z + p.w);
+                c = njx + nin;                                   // accumulator init of pair u+2
+                dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
+                __builtin_amdgcn_sched_barrier(0);
+
                 if (SCORE) {
 #pragma unroll
-                    for (int mb = 0; mb < KB; ++mb) {
-                        f32x4 acc = tacc[t][mb];
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].x, p.x, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].y, p.y, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].z, p.z, acc, 0, 0, 0);
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb].w, p.w, acc, 0, 0, 0);
-                        tacc[t][mb] = acc;
+                    for (int i = 0; i < NM; ++i) {
+                        const int v = i / KB, mb = i % KB;     // the KB accumulator chains interleave
+                        tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tacc[t][mb], 0, 0, 0);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         };
         const int dt0 = (int)(row0 / kTile);      // tile index of this wave's first row tile
 
         for (int jt = t_begin; jt < t_end; ++jt) {
-            f32x4 a1n[KB], a2n[SCORE ? KB : 1], njn;
             load_tile(min(jt + 1, t_end - 1), a1n, a2n, njn);   // prefetch (clamped: always in bounds)
+            __builtin_amdgcn_sched_barrier(0);                   // keep the loads a whole iteration ahead
 
             if (SELF && (unsigned)(jt - dt0) < (unsigned)NI)    // wave-uniform
-                step(std::true_type{}, jt - dt0);
+                iteration(std::true_type{}, jt - dt0);
             else
-                step(std::false_type{}, 0);
+                iteration(std::false_type{}, 0);
 
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) a1[kb] = a1n[kb];
-            if (SCORE) {
 #pragma unroll
-                for (int mb = 0; mb < KB; ++mb) a2[mb] = a2n[mb];
-            }
+            for (int mb = 0; mb < KT; ++mb) a2[mb] = a2n[mb];
             nj = njn;
         }
+        // The pipeline has started pair (t_end, 0) on a re-read of the last tile; it is dropped.
     }
 
     // Partial results of this split: T^T accumulator (lane (r, g), register v) = coordinate
@@ -432,9 +457,8 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
         cand[nc++] = 4; cand[nc++] = 2; cand[nc++] = 1;
     } else {
         const int kb = p.dp / 16;
-        const int top = score ? (kb == 1 ? 8 : kb == 2 ? 4 : kb <= 4 ? 2 : 1)
-                              : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
-        for (int v = top; v >= 1; v /= 2) cand[nc++] = v;
+        const int top = score ? (kb == 1 ? 8 : kb == 2 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+        for (int v = top; v >= 2; v /= 2) cand[nc++] = v;
     }
     const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
     const int forced_split = env_int(score ? "SDKDE_SCORE_SPLIT" : "SDKDE_EVAL_SPLIT", 0);
@@ -549,28 +573,28 @@ int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
         const int kb = p.dp / 16;
         switch (kb) {
             case 1:
-                switch (p.ni) { SDKDE_CASE_NI(1, 16) SDKDE_CASE_NI(1, 8) SDKDE_CASE_NI(1, 4) SDKDE_CASE_NI(1, 2) SDKDE_CASE_NI(1, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(1, 16) SDKDE_CASE_NI(1, 8) SDKDE_CASE_NI(1, 4) SDKDE_CASE_NI(1, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 2:
-                switch (p.ni) { SDKDE_CASE_NI(2, 8) SDKDE_CASE_NI(2, 4) SDKDE_CASE_NI(2, 2) SDKDE_CASE_NI(2, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(2, 8) SDKDE_CASE_NI(2, 4) SDKDE_CASE_NI(2, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 3:
-                switch (p.ni) { SDKDE_CASE_NI(3, 4) SDKDE_CASE_NI(3, 2) SDKDE_CASE_NI(3, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(3, 4) SDKDE_CASE_NI(3, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 4:
-                switch (p.ni) { SDKDE_CASE_NI(4, 4) SDKDE_CASE_NI(4, 2) SDKDE_CASE_NI(4, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(4, 4) SDKDE_CASE_NI(4, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 5:
-                switch (p.ni) { SDKDE_CASE_NI(5, 2) SDKDE_CASE_NI(5, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(5, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 6:
-                switch (p.ni) { SDKDE_CASE_NI(6, 2) SDKDE_CASE_NI(6, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(6, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 7:
-                switch (p.ni) { SDKDE_CASE_NI(7, 2) SDKDE_CASE_NI(7, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(7, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 8:
-                switch (p.ni) { SDKDE_CASE_NI(8, 2) SDKDE_CASE_NI(8, 1) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(8, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             default: return SDKDE_EUNSUPPORTED;
         }
