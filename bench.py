@@ -27,11 +27,15 @@ def cpu_baseline(x, q, h, budget_s=15.0):
     import oracle
     n, d = x.shape
     m = q.shape[0]
-    cal_rows = max(8, min(n, int(2e7 // n) + 1))
-    t0 = time.perf_counter()
-    oracle.score(x, h, points=x[:cal_rows])
-    cal = time.perf_counter() - t0
-    rate = cal_rows * n / max(cal, 1e-9)
+    cal_rows, rate = 16, 0.0
+    while True:                      # calibrate on a run long enough to amortise thread start-up
+        cal_rows = min(n, cal_rows * 4)
+        t0 = time.perf_counter()
+        oracle.score(x, h, points=x[:cal_rows])
+        cal = time.perf_counter() - t0
+        rate = cal_rows * n / max(cal, 1e-9)
+        if cal >= 0.5 or cal_rows == n:
+            break
     rows = int(min(n, max(cal_rows, budget_s * rate / (n * (1.0 + m / n)))))
     qrows = int(min(m, max(1, round(rows * m / n))))
     t0 = time.perf_counter()

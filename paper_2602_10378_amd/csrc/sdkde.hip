@@ -29,6 +29,7 @@ constexpr int kRowPad = 1024;          // row padding of every prepared array (>
 constexpr float kPadNorm = -1.0e30f;   // "-|x|^2" of a padding sample: exp2 of it is exactly 0
 constexpr float kPadCoord = 1.0e18f;   // thin-d padding coordinate: squared distance ~1e36, exp2(-that) = 0
 constexpr int kMeanBlocks = 128;
+constexpr int kFlushTiles = 64;         // sample tiles between folds of the running sums (power of two)
 constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3, MFMA path above
 
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
@@ -164,13 +165,16 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         ni[t] = pn[row];
     }
 
-    f32x4 tacc[NI][KT];
-    float dacc[NI];
+    // Two-level accumulation: the running sums (tacc, dacc) are folded into (tsum, dsum) every
+    // kFlushTiles sample tiles, so no fp32 accumulator sees more than a short chain of additions
+    // at its own magnitude (keeps the rounding of T and D well below the cancellation in T/D - x).
+    f32x4 tacc[NI][KT], tsum[NI][KT];
+    float dacc[NI], dsum[NI];
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
-        dacc[t] = 0.0f;
+        dacc[t] = dsum[t] = 0.0f;
 #pragma unroll
-        for (int mb = 0; mb < KT; ++mb) tacc[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int mb = 0; mb < KT; ++mb) tacc[t][mb] = tsum[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
     const int t_begin = split * tiles_per_split;
@@ -273,8 +277,27 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 #pragma unroll
             for (int mb = 0; mb < KT; ++mb) a2[mb] = a2n[mb];
             nj = njn;
+
+            if (((jt - t_begin) & (kFlushTiles - 1)) == kFlushTiles - 1) {    // wave-uniform
+#pragma unroll
+                for (int t = 0; t < NI; ++t) {
+                    dsum[t] += dacc[t];
+                    dacc[t] = 0.0f;
+#pragma unroll
+                    for (int mb = 0; mb < KT; ++mb) {
+                        tsum[t][mb] += tacc[t][mb];
+                        tacc[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            }
         }
         // The pipeline has started pair (t_end, 0) on a re-read of the last tile; it is dropped.
+    }
+#pragma unroll
+    for (int t = 0; t < NI; ++t) {
+        dsum[t] += dacc[t];
+#pragma unroll
+        for (int mb = 0; mb < KT; ++mb) tsum[t][mb] += tacc[t][mb];
     }
 
     // Partial results of this split: T^T accumulator (lane (r, g), register v) = coordinate
@@ -285,12 +308,12 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         if (SCORE) {
             float* dst = part_t + ((int64_t)split * m_pad + row) * DP + g * 4;
 #pragma unroll
-            for (int mb = 0; mb < KB; ++mb) *reinterpret_cast<f32x4*>(dst + mb * 16) = tacc[t][mb];
+            for (int mb = 0; mb < KB; ++mb) *reinterpret_cast<f32x4*>(dst + mb * 16) = tsum[t][mb];
         }
-        float dsum = dacc[t];
-        dsum += __shfl_xor(dsum, 16);
-        dsum += __shfl_xor(dsum, 32);
-        if (g == 0) part_d[(int64_t)split * m_pad + row] = dsum;
+        float dtot = dsum[t];
+        dtot += __shfl_xor(dtot, 16);
+        dtot += __shfl_xor(dtot, 32);
+        if (g == 0) part_d[(int64_t)split * m_pad + row] = dtot;
     }
 }
 

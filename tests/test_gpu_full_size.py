@@ -1,0 +1,68 @@
+"""Parity at the benchmark's full sizes (configs C2-C5), in the launch configuration bench.py
+times.  The oracle cannot cover all n^2 pairs there, so it computes sampled outputs one by one:
+random rows plus the rows at tile / row-block / split boundaries, each against ALL n samples."""
+import numpy as np
+import pytest
+
+import oracle
+import sdkde_inputs
+from parity import assert_density_close, assert_log_density_close, assert_score_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(count, extra, seed=0):
+    edges = [0, 1, 15, 16, 17, 63, 64, 127, 128, 255, 256, 511, 512, 1023, 1024, 2047, 2048]
+    rows = {e for e in edges if e < count}
+    rows |= {count - 1 - e for e in edges if e < count}
+    # sample-tile ranges of the splits start at multiples of (tiles per split) * 16
+    rows |= {(count // 8) * k for k in range(1, 8)} | {(count // 8) * k - 1 for k in range(1, 8)}
+    rng = np.random.default_rng(seed)
+    rows |= set(int(v) for v in rng.integers(0, count, size=extra))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_sampled_parity(name):
+    import torch
+    import paper_2602_10378_amd as P
+    print(f"full-size {name}", flush=True)
+    x, q, h = sdkde_inputs.make(name, seed=0)
+    n, d = x.shape
+    m = q.shape[0]
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ws = P.make_workspace(n, m, d)
+
+    # score at the samples: sampled rows against the oracle
+    s = P.sdkde_score(xd, h, workspace=ws)
+    rows = _sample_rows(n, 96)
+    s_ref = oracle.score(x, h, points=x[rows])
+    got = s[torch.from_numpy(rows).cuda()].cpu().numpy()
+    worst, frob = assert_score_close(got, s_ref, f"{name} score")
+    print(f"{name}: score on {len(rows)} rows: worst {worst:.3g} of allowance, rel frobenius {frob:.3g}", flush=True)
+
+    # debias: full array, elementwise, on the library's own score as input to both sides is not
+    # allowed (oracle inputs never come from the GPU), so a seeded synthetic score is used
+    rng = np.random.default_rng(5)
+    fake = rng.standard_normal(x.shape).astype(np.float32)
+    x_sd = P.sdkde_debias(xd, torch.from_numpy(fake).cuda(), h).cpu().numpy()
+    ref = oracle.debias(x, fake, h)
+    scale = np.abs(x).astype(np.float64) + 0.5 * h * h * np.abs(fake)
+    assert np.max(np.abs(x_sd - ref) / scale) < 2.0**-22               # roundings of the fp32 constant and fma
+
+    # eval: KDE of the (unshifted) samples at sampled queries
+    dens, logd = P.sdkde_eval(xd, qd, h, want="both", workspace=ws)
+    qrows = _sample_rows(m, 96, seed=1)
+    logp_ref = oracle.eval_log_density(x, q[qrows], h)
+    idx = torch.from_numpy(qrows).cuda()
+    e_log = assert_log_density_close(logd[idx].cpu().numpy(), logp_ref, f"{name} eval")
+    e_den = assert_density_close(dens[idx].cpu().numpy(), logp_ref, f"{name} eval")
+    print(f"{name}: eval on {len(qrows)} queries: log err {e_log:.3g}, density rel err {e_den:.3g}", flush=True)
+
+    # whole pipeline properties that hold at any size
+    x_sd_gpu = P.sdkde_debias(xd, s, h)
+    assert torch.isfinite(s).all() and torch.isfinite(x_sd_gpu).all()
+    lo, hi = xd.min(0).values, xd.max(0).values
+    assert bool(((x_sd_gpu >= lo - 1e-4) & (x_sd_gpu <= hi + 1e-4)).all()), "shifted sample left the data's bounding box"
+    _, logd_sd = P.sdkde_eval(x_sd_gpu, qd, h, want="log", workspace=ws)
+    assert torch.isfinite(logd_sd).all()
