@@ -16,6 +16,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+# HBM bytes per launch of the score main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
+# read counter x2 and write counter x1 after calibration on the debias kernel): profiles/pipeline_<config>_*.txt
+SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4584784.9 * 2 + 557056.0) * 1024}
 PAPER_PAIRS_PER_S_C5 = (1048576.0**2 + 131072.0 * 1048576.0) / 2.3   # paper: 2.3 s on one RTX A6000 (TF32)
 
 
@@ -125,7 +128,8 @@ def main():
     }
     if d > 3:
         out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                           "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                           "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get(args.config) if (args.n is None and args.m is None) else None,
                            "kernel": "pair_mfma_kernel (score)", "launch_ms": score_avg_ms,
                            "flops_per_launch": score_flops}
     else:

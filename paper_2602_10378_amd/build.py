@@ -9,6 +9,8 @@ ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "sdkde.hip")]
 HEADERS = [os.path.join(ROOT, "include", "sdkde.h")]
 LIBRARY = os.path.join(HERE, "libsdkde.so")
+PEAKS_SOURCE = os.path.join(HERE, "csrc", "peaks.hip")
+PEAKS_BINARY = os.path.join(HERE, "sdkde_peaks")     # micro-benchmark of the instruction rates that bound the kernels
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -37,6 +39,11 @@ def build(force: bool = True, verbose: bool = False) -> str:
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + proc.stdout)
+    flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
+    proc = subprocess.run([hipcc, *flags, "-o", PEAKS_BINARY, PEAKS_SOURCE], stdout=subprocess.PIPE,
+                          stderr=subprocess.STDOUT, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed (peaks):\n" + proc.stdout)
     return LIBRARY
 
 
