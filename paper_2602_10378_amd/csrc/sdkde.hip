@@ -123,9 +123,10 @@ __global__ __launch_bounds__(kBlock) void prep_thin_kernel(const float* __restri
 // first MFMA is likewise permuted (MFMA kk contracts coordinates {kk, 4+kk, 8+kk, 12+kk} of each
 // 16-column block) so that both operands are plain float4 row loads.
 //
-// SELF (score at the samples themselves): the pair (i, i) is left out of D and T and the
-// epilogue restores it analytically (phi_ii = 1), because T_i/D_i - x_i would otherwise cancel
-// against the large self term whenever a point has few neighbours.
+// SELF (score at the samples themselves): the pair (i, i) must stay out of D and T, because
+// T_i/D_i - x_i would otherwise cancel against the large self term whenever a point has few
+// neighbours; the epilogue restores it analytically (phi_ii = 1).  This kernel therefore skips
+// the NI sample tiles that are the wave's own row tiles; pair_diag_kernel covers them.
 //
 // Grid: blockIdx.x = row_block * S + split; each workgroup handles RB = 64*NI rows and the
 // sample tiles [split*tiles_per_split, min(ntiles, (split+1)*tiles_per_split)).  With S a
@@ -134,6 +135,49 @@ __global__ __launch_bounds__(kBlock) void prep_thin_kernel(const float* __restri
 // All arrays are padded so that every access below is in bounds:
 //   ps, pn : m_pad rows (multiple of kRowPad >= RB);  xs, xt, xn : ntiles*16 rows.
 // ------------------------------------------------------------------------------------------
+
+// Row-tile operands of one wave: B operand 2 * p~ (lane (r, g) holds coordinates 16kb + 4g .. +3
+// of row r) and -|p~|^2 for NI row tiles starting at row0.
+template <int KB, int NI>
+__device__ __forceinline__ void load_row_tiles(const float* __restrict__ ps, const float* __restrict__ pn,
+                                               int64_t row0, int r, int g, f32x4 (&b)[NI][KB], float (&ni)[NI])
+{
+    constexpr int DP = KB * 16;
+#pragma unroll
+    for (int t = 0; t < NI; ++t) {
+        const int64_t row = row0 + t * kTile + r;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            f32x4 v = *reinterpret_cast<const f32x4*>(ps + row * DP + kb * 16 + g * 4);
+            b[t][kb] = v * 2.0f;
+        }
+        ni[t] = pn[row];
+    }
+}
+
+// Writes one wave's partial sums: T^T accumulator (lane (r, g), register v) = coordinate
+// 16mb + 4g + v of row r; D needs the sum over the four lane groups g.
+template <int KB, int NI, bool SCORE>
+__device__ __forceinline__ void store_partials(float* __restrict__ part_t, float* __restrict__ part_d, int64_t slot,
+                                               int64_t m_pad, int64_t row0, int r, int g,
+                                               const f32x4 (&tsum)[NI][SCORE ? KB : 1], const float (&dsum)[NI])
+{
+    constexpr int DP = KB * 16;
+#pragma unroll
+    for (int t = 0; t < NI; ++t) {
+        const int64_t row = row0 + t * kTile + r;
+        if (SCORE) {
+            float* dst = part_t + (slot * m_pad + row) * DP + g * 4;
+#pragma unroll
+            for (int mb = 0; mb < KB; ++mb) *reinterpret_cast<f32x4*>(dst + mb * 16) = tsum[t][mb];
+        }
+        float dtot = dsum[t];
+        dtot += __shfl_xor(dtot, 16);
+        dtot += __shfl_xor(dtot, 32);
+        if (g == 0) part_d[slot * m_pad + row] = dtot;
+    }
+}
+
 template <int KB, int NI, bool SCORE, bool SELF>
 __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const float* __restrict__ ps, const float* __restrict__ pn, const float* __restrict__ xs,
@@ -151,19 +195,9 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const int64_t row_block = blockIdx.x / nsplit;
     const int64_t row0 = (row_block * kWavesPerBlock + wave) * (NI * kTile);
 
-    // B operand: 2 * p~ for NI row tiles; lane (r, g) holds coordinates 16kb + 4g .. +3 of row r.
     f32x4 b[NI][KB];
     float ni[NI];
-#pragma unroll
-    for (int t = 0; t < NI; ++t) {
-        const int64_t row = row0 + t * kTile + r;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            f32x4 v = *reinterpret_cast<const f32x4*>(ps + row * DP + kb * 16 + g * 4);
-            b[t][kb] = v * 2.0f;
-        }
-        ni[t] = pn[row];
-    }
+    load_row_tiles<KB, NI>(ps, pn, row0, r, g, b, ni);
 
     // Two-level accumulation: the running sums (tacc, dacc) are folded into (tsum, dsum) every
     // kFlushTiles sample tiles, so no fp32 accumulator sees more than a short chain of additions
@@ -177,23 +211,46 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         for (int mb = 0; mb < KT; ++mb) tacc[t][mb] = tsum[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
+    // ntiles, tiles_per_split and NI are even (host side), so every span of sample tiles below
+    // has even length and the loop can alternate two operand register sets without copies.
     const int t_begin = split * tiles_per_split;
     const int t_end = min(ntiles, t_begin + tiles_per_split);
+    const int dt0 = (int)(row0 / kTile);          // the wave's own row tiles are sample tiles dt0 .. dt0+NI-1
 
-    if (t_begin < t_end) {
-        f32x4 a1[KB], a2[KT], nj;          // operands of the current sample tile
-        f32x4 a1n[KB], a2n[KT], njn;       // ... of the next one (prefetched)
-        auto load_tile = [&](int jt, f32x4 (&la1)[KB], f32x4 (&la2)[KT], f32x4& lnj) {
-            const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
+    // Operands of one sample tile, as each lane holds them.
+    struct Operands {
+        f32x4 a1[KB];     // first contraction, A: lane (r, g) = coordinates 16kb + 4g .. +3 of sample r
+        f32x4 a2[KT];     // second contraction, A: lane (r, g) = coordinate 16mb + r of samples 4g .. 4g+3
+        f32x4 nj;         // -|x|^2 of samples 4g .. 4g+3
+    };
+    Operands set_a, set_b;
+    f32x4 creg[2], ph[2];
+
+    // SELF: two spans, before and after the wave's own tiles; otherwise the whole range.
+    for (int span = 0; span < (SELF ? 2 : 1); ++span) {
+        int s_begin = t_begin, s_end = t_end;
+        if (SELF) {
+            if (span == 0) s_end = min(t_end, dt0);
+            else s_begin = max(t_begin, dt0 + NI);
+        }
+        if (s_begin >= s_end) continue;
+
+        const int t_last = s_end - 1;     // prefetches past the span re-read its last tile (in bounds)
+        auto load_a1 = [&](int jt, Operands& o) {
+            const float* xrow = xs + ((int64_t)min(jt, t_last) * kTile + r) * DP + g * 4;
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) la1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
+            for (int kb = 0; kb < KB; ++kb) o.a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
+        };
+        auto load_a2 = [&](int jt, Operands& o) {
             if (SCORE) {
-                const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
+                const float* trow = xt + ((int64_t)min(jt, t_last) * DP + r) * kTile + g * 4;
 #pragma unroll
                 for (int mb = 0; mb < KB; ++mb)
-                    la2[mb] = *reinterpret_cast<const f32x4*>(trow + mb * 16 * kTile);
+                    o.a2[mb] = *reinterpret_cast<const f32x4*>(trow + mb * 16 * kTile);
             }
-            lnj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
+        };
+        auto load_nj = [&](int jt, Operands& o) {
+            o.nj = *reinterpret_cast<const f32x4*>(xn + (int64_t)min(jt, t_last) * kTile + g * 4);
         };
 
         // Software pipeline over the flattened sequence of (sample tile, row tile) pairs u:
@@ -205,49 +262,52 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         // switches between MFMA and VALU), so VALU work is gathered into one clump per pair
         // instead of being interleaved, and each clump only touches results that are at least
         // one MFMA group old, so it never waits.  creg[u & 1] holds the exponent tile of pair u,
-        // ph[u & 1] its Phi^T tile.  Scheduling barriers pin the three groups.
-        f32x4 creg[2], ph[2];
-        load_tile(t_begin, a1, a2, nj);
-        creg[0] = nj + ni[0];
+        // ph[u & 1] its Phi^T tile.  Scheduling barriers pin the groups.
+        //
+        // Operand prefetch: two register sets alternate between "current" and "next" sample tile.
+        // Each part of a set is reloaded for the tile after next as soon as its last reader has
+        // issued, which puts every load about one full iteration (NI pairs) ahead of its use.
+        load_a1(s_begin, set_a);
+        load_a2(s_begin, set_a);
+        load_nj(s_begin, set_a);
+        creg[0] = set_a.nj + ni[0];
 #pragma unroll
         for (int i = 0; i < NM; ++i)
-            creg[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i / 4][i % 4], b[0][i / 4][i % 4], creg[0], 0, 0, 0);
-        creg[1] = nj + ni[1];
+            creg[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(set_a.a1[i / 4][i % 4], b[0][i / 4][i % 4], creg[0], 0, 0, 0);
+        creg[1] = set_a.nj + ni[1];
+        load_a1(s_begin + 1, set_b);
+        load_nj(s_begin + 1, set_b);
 
-        // One sample tile against all NI row tiles.  DIAG: the sample tile is this wave's own row
-        // tile number dt; the pair of a point with itself is left out of both sums there.
-        auto iteration = [&](auto diag_tag, int dt) {
-            constexpr bool DIAG = decltype(diag_tag)::value;
+        // Sample tile jt (operands in cur; those of jt+1 arriving in nxt) against all NI row tiles.
+        auto iteration = [&](int jt, Operands& cur, Operands& nxt) {
+            load_a2(jt + 1, nxt);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < NI; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
+                const int slot = t & 1;
                 const bool wrap1 = t + 1 >= NI, wrap2 = t + 2 >= NI;     // compile-time after unrolling
-                f32x4& c = creg[cur];
-                f32x4& phi = ph[cur];
+                f32x4& c = creg[slot];
+                f32x4& phi = ph[slot];
                 const float nin = ni[(t + 2) % NI];
-                const f32x4& njx = wrap2 ? njn : nj;
-                const bool mine = DIAG && t == dt;
 
+                if (t == NI - 2) {              // cur.nj was last read by the clump of t = NI - 3
+                    load_nj(jt + 2, cur);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
 #pragma unroll
                 for (int i = 0; i < NM; ++i) {
                     const int kb = i / 4, kk = i % 4;
-                    const float av = wrap1 ? a1n[kb][kk] : a1[kb][kk];
-                    creg[nxt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b[(t + 1) % NI][kb][kk], creg[nxt], 0, 0, 0);
+                    const float av = wrap1 ? nxt.a1[kb][kk] : cur.a1[kb][kk];
+                    creg[slot ^ 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b[(t + 1) % NI][kb][kk], creg[slot ^ 1], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
+                if (t == NI - 2) load_a1(jt + 2, cur);    // cur.a1 was last read by the MFMAs above
 
                 phi.x = __builtin_amdgcn_exp2f(c.x);
                 phi.y = __builtin_amdgcn_exp2f(c.y);
                 phi.z = __builtin_amdgcn_exp2f(c.z);
                 phi.w = __builtin_amdgcn_exp2f(c.w);
-                if (DIAG) {
-                    // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
-                    phi.x = (mine && g * 4 + 0 == r) ? 0.0f : phi.x;
-                    phi.y = (mine && g * 4 + 1 == r) ? 0.0f : phi.y;
-                    phi.z = (mine && g * 4 + 2 == r) ? 0.0f : phi.z;
-                    phi.w = (mine && g * 4 + 3 == r) ? 0.0f : phi.w;
-                }
-                c = njx + nin;                                   // accumulator init of pair u+2
+                c = (wrap2 ? nxt.nj : cur.nj) + nin;             // accumulator init of pair u+2
                 dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
                 __builtin_amdgcn_sched_barrier(0);
 
@@ -255,30 +315,17 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 #pragma unroll
                     for (int i = 0; i < NM; ++i) {
                         const int v = i / KB, mb = i % KB;     // the KB accumulator chains interleave
-                        tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tacc[t][mb], 0, 0, 0);
+                        tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur.a2[mb][v], phi[v], tacc[t][mb], 0, 0, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         };
-        const int dt0 = (int)(row0 / kTile);      // tile index of this wave's first row tile
 
-        for (int jt = t_begin; jt < t_end; ++jt) {
-            load_tile(min(jt + 1, t_end - 1), a1n, a2n, njn);   // prefetch (clamped: always in bounds)
-            __builtin_amdgcn_sched_barrier(0);                   // keep the loads a whole iteration ahead
-
-            if (SELF && (unsigned)(jt - dt0) < (unsigned)NI)    // wave-uniform
-                iteration(std::true_type{}, jt - dt0);
-            else
-                iteration(std::false_type{}, 0);
-
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) a1[kb] = a1n[kb];
-#pragma unroll
-            for (int mb = 0; mb < KT; ++mb) a2[mb] = a2n[mb];
-            nj = njn;
-
-            if (((jt - t_begin) & (kFlushTiles - 1)) == kFlushTiles - 1) {    // wave-uniform
+        for (int jt = s_begin; jt < s_end; jt += 2) {
+            iteration(jt, set_a, set_b);
+            iteration(jt + 1, set_b, set_a);
+            if (((jt + 1 - s_begin) & (kFlushTiles - 1)) == kFlushTiles - 1) {    // wave-uniform
 #pragma unroll
                 for (int t = 0; t < NI; ++t) {
                     dsum[t] += dacc[t];
@@ -291,7 +338,7 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                 }
             }
         }
-        // The pipeline has started pair (t_end, 0) on a re-read of the last tile; it is dropped.
+        // The pipeline has started pair (s_end, 0) on a re-read of the last tile; it is dropped.
     }
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
@@ -299,22 +346,75 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 #pragma unroll
         for (int mb = 0; mb < KT; ++mb) tsum[t][mb] += tacc[t][mb];
     }
+    store_partials<KB, NI, SCORE>(part_t, part_d, split, m_pad, row0, r, g, tsum, dsum);
+}
 
-    // Partial results of this split: T^T accumulator (lane (r, g), register v) = coordinate
-    // 16mb + 4g + v of row r; D needs the sum over the four lane groups g.
+// Diagonal blocks of the score at the samples themselves: every wave pairs its NI row tiles with
+// the same NI tiles taken as samples, leaving out the pair of each point with itself, and writes
+// the sums into partial slot `slot` (one past the splits of pair_mfma_kernel).  Same operand
+// layouts as above; a plain loop, since this is NI*16 pairs per row out of n.
+// Grid: one workgroup per row block, as in the main kernel.
+template <int KB, int NI>
+__global__ __launch_bounds__(kBlock) void pair_diag_kernel(
+    const float* __restrict__ xs, const float* __restrict__ xt, const float* __restrict__ xn,
+    float* __restrict__ part_t, float* __restrict__ part_d, int ntiles, int slot, int64_t m_pad)
+{
+    constexpr int DP = KB * 16;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int r = lane & 15, g = lane >> 4;
+    const int64_t row0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * (NI * kTile);
+    const int dt0 = (int)(row0 / kTile);
+
+    f32x4 b[NI][KB];
+    float ni[NI];
+    load_row_tiles<KB, NI>(xs, xn, row0, r, g, b, ni);
+    f32x4 tsum[NI][KB];
+    float dsum[NI];
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
-        const int64_t row = row0 + t * kTile + r;
-        if (SCORE) {
-            float* dst = part_t + ((int64_t)split * m_pad + row) * DP + g * 4;
+        dsum[t] = 0.0f;
 #pragma unroll
-            for (int mb = 0; mb < KB; ++mb) *reinterpret_cast<f32x4*>(dst + mb * 16) = tsum[t][mb];
-        }
-        float dtot = dsum[t];
-        dtot += __shfl_xor(dtot, 16);
-        dtot += __shfl_xor(dtot, 32);
-        if (g == 0) part_d[(int64_t)split * m_pad + row] = dtot;
+        for (int mb = 0; mb < KB; ++mb) tsum[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+
+    for (int dt = 0; dt < NI; ++dt) {
+        const int jt = dt0 + dt;
+        if (jt >= ntiles) break;               // rows past the last sample tile are padding
+        f32x4 a1[KB], a2[KB];
+        const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
+        const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
+            a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * kTile);
+        }
+        const f32x4 nj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
+#pragma unroll
+        for (int t = 0; t < NI; ++t) {
+            f32x4 c = nj + ni[t];
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb][kk], b[t][kb][kk], c, 0, 0, 0);
+            f32x4 phi;
+            // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
+            const bool own = t == dt;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const float e = __builtin_amdgcn_exp2f(c[v]);
+                phi[v] = (own && g * 4 + v == r) ? 0.0f : e;
+            }
+            dsum[t] += (phi.x + phi.y) + (phi.z + phi.w);
+#pragma unroll
+            for (int mb = 0; mb < KB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tsum[t][mb], 0, 0, 0);
+        }
+    }
+    store_partials<KB, NI, true>(part_t, part_d, slot, m_pad, row0, r, g, tsum, dsum);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -469,7 +569,7 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
     p.dp = p.thin ? d : (int)round_up(d, 16);
     p.n_pad = round_up(n, kRowPad);
     p.m_pad = round_up(m > 0 ? m : 1, kRowPad);
-    p.ntiles = (int)((n + kTile - 1) / kTile);
+    p.ntiles = (int)((n + 2 * kTile - 1) / (2 * kTile)) * 2;   // even: the pair kernel alternates two operand sets
     const int max_split = p.ntiles >= 32 ? p.ntiles / 16 : 1;   // at least 16 tiles per split
 
     // Candidate row-tile counts, largest (most operand reuse) first; a smaller one is taken
@@ -480,13 +580,22 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
         cand[nc++] = 4; cand[nc++] = 2; cand[nc++] = 1;
     } else {
         const int kb = p.dp / 16;
-        const int top = score ? (kb == 1 ? 8 : kb == 2 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+        // measured: more row tiles per wave (operand reuse) beats a second wave per SIMD once dp >= 48
+        const int top = score ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
         for (int v = top; v >= 2; v /= 2) cand[nc++] = v;
     }
     const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
     const int forced_split = env_int(score ? "SDKDE_SCORE_SPLIT" : "SDKDE_EVAL_SPLIT", 0);
-    for (int q = 0; q < nc; ++q)
-        if (cand[q] == forced_ni) { cand[0] = forced_ni; nc = 1; }
+    {
+        // a forced value must be one the dispatch tables below instantiate
+        const int kb = p.thin ? 0 : p.dp / 16;
+        const int widest = p.thin ? 4 : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+        const int narrowest = p.thin ? 1 : 2;
+        if (forced_ni >= narrowest && forced_ni <= widest && (forced_ni & (forced_ni - 1)) == 0) {
+            cand[0] = forced_ni;
+            nc = 1;
+        }
+    }
 
     for (int k = 0; k < nc; ++k) {
         p.ni = cand[k];
@@ -505,6 +614,7 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
         if (p.row_blocks * p.nsplit >= kTargetBlocks / 2) break;
     }
     p.tiles_per_split = (p.ntiles + p.nsplit - 1) / p.nsplit;
+    p.tiles_per_split += p.tiles_per_split & 1;
     return p;
 }
 
@@ -540,8 +650,10 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base)
         w.ps = w.xs;
         w.pn = w.xn;
     }
-    w.part_t = score ? (float*)take(sizeof(float) * (size_t)p.nsplit * p.m_pad * p.dp) : nullptr;
-    w.part_d = (float*)take(sizeof(float) * (size_t)p.nsplit * p.m_pad);
+    // one slot per split, plus the diagonal-block slot of the score at the samples themselves
+    const size_t slots = (size_t)p.nsplit + ((score && !separate_points && !p.thin) ? 1 : 0);
+    w.part_t = score ? (float*)take(sizeof(float) * slots * p.m_pad * p.dp) : nullptr;
+    w.part_d = (float*)take(sizeof(float) * slots * p.m_pad);
     w.bytes = off;
     return w;
 }
@@ -569,9 +681,14 @@ int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
     // Host-side shape check: every row the grid touches exists in the padded arrays.
     if (p.row_blocks * p.rows_per_block > p.m_pad || (int64_t)p.ntiles * kTile > p.n_pad) return SDKDE_EINVAL;
 
-#define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                   \
-    hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, SCORE, SELF>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt, \
-                       w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad)
+#define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                               \
+    do {                                                                                                          \
+        hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, SCORE, SELF>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt, \
+                           w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad);             \
+        if constexpr (SCORE && SELF)                                                                              \
+            hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_>), dim3((unsigned)p.row_blocks), block, 0, st, w.xs,    \
+                               w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                      \
+    } while (0)
 #define SDKDE_LAUNCH_THIN(D_, R_)                                                                  \
     hipLaunchKernelGGL((pair_thin_kernel<D_, R_, SCORE>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
                        w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad)
@@ -723,7 +840,8 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     const int64_t total = m * (int64_t)d;
     const float inv_ah2 = (float)(1.0 / (a * h * h));
     hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
-                       w.part_t, w.part_d, w.ps, p.nsplit, m, p.m_pad, d, p.dp, p.thin ? 1 : (self ? 2 : 0), inv_ah2, score_out);
+                       w.part_t, w.part_d, w.ps, p.nsplit + ((self && !p.thin) ? 1 : 0), m, p.m_pad, d, p.dp,
+                       p.thin ? 1 : (self ? 2 : 0), inv_ah2, score_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
