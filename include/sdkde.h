@@ -86,6 +86,18 @@ int sdkde_eval(const float *samples_sd, int64_t n, const float *queries, int64_t
                double h, float *density_out, float *log_density_out, void *workspace,
                size_t workspace_bytes, uint32_t flags, void *stream);
 
+/*
+ * Laplace-corrected KDE (Laplace-corrected KDE section: K_h^LC(x) = K_h(x) (1 + d/2 - |x|^2 / 2h^2),
+ * p_LC(q) = (1/n) sum_j K_h^LC(q - x_j)), with the affine factor applied inside the same pass that
+ * forms exp(-|q - x_j|^2 / 2h^2) (the fused "Flash-Laplace-KDE" of that section).  It takes the
+ * UNSHIFTED samples and needs no score pass.  The estimate can be negative; density_out [m] is
+ * signed and underflows to 0 where |p_LC| is below the fp32 range.  Arguments otherwise as in
+ * sdkde_eval; sdkde_workspace_bytes(n, m, d) covers it.
+ */
+int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, int64_t m, int32_t d,
+                       double h, float *density_out, void *workspace, size_t workspace_bytes,
+                       uint32_t flags, void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *sdkde_status_string(int status);
 

@@ -38,6 +38,7 @@ def _load():
         lib.sdkde_oracle_debias.argtypes = [dp, dp, i64, i32, f64, dp]
         lib.sdkde_oracle_eval.argtypes = [dp, i64, dp, i64, i32, f64, dp, dp]
         lib.sdkde_oracle_eval_laplace.argtypes = [dp, i64, dp, i64, i32, f64, dp]
+        lib.sdkde_oracle_eval_laplace_abs.argtypes = [dp, i64, dp, i64, i32, f64, dp]
         _lib = lib
     return _lib
 
@@ -113,6 +114,15 @@ def eval_laplace_density(samples, queries, h: float) -> np.ndarray:
     out = np.empty(q.shape[0], dtype=np.float64)
     _check(_load().sdkde_oracle_eval_laplace(_p(x), x.shape[0], _p(q), q.shape[0], x.shape[1],
                                              float(h), _p(out)), "eval_laplace")
+    return out
+
+
+def eval_laplace_abs_density(samples, queries, h: float) -> np.ndarray:
+    """Sum of K_h |1 + d/2 - r^2/2h^2| / n: the scale of the terms the signed Laplace sum cancels."""
+    x, q = _f64(samples), _f64(queries)
+    out = np.empty(q.shape[0], dtype=np.float64)
+    _check(_load().sdkde_oracle_eval_laplace_abs(_p(x), x.shape[0], _p(q), q.shape[0], x.shape[1],
+                                                 float(h), _p(out)), "eval_laplace_abs")
     return out
 
 

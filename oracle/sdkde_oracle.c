@@ -108,9 +108,10 @@ int sdkde_oracle_debias(const double *X, const double *S, int64_t n, int32_t d, 
  *   p(q) = 1/(n h^d) sum_j phi((q - x_j)/h),  phi(u) = (2 pi)^(-d/2) exp(-||u||^2 / 2).
  * Evaluated in log space: log p = amax + log sum_j exp(a_j - amax) - log n - d log h
  * - (d/2) log(2 pi).  Either output pointer may be NULL.
- * laplace != 0 multiplies each term by (1 + d/2 - ||q - x_j||^2 / 2h^2), the
+ * laplace == 1 multiplies each term by (1 + d/2 - ||q - x_j||^2 / 2h^2), the
  * Laplace-corrected kernel K_h^LC; the sum can then be negative, so only `dens` is
- * written (logdens must be NULL).
+ * written (logdens must be NULL).  laplace == 2 uses the absolute value of that factor:
+ * the magnitude against which the rounding of the signed sum is judged.
  * Xs: samples [n,d]; Q: queries [m,d]; logdens, dens: out [m].
  */
 static int eval_impl(const double *Xs, int64_t n, const double *Q, int64_t m, int32_t d,
@@ -143,8 +144,11 @@ static int eval_impl(const double *Xs, int64_t n, const double *Q, int64_t m, in
                     if (dens) dens[i] = exp(lp);
                 } else {
                     /* a_j = -r^2/2h^2, so the affine factor is 1 + d/2 + a_j */
-                    for (int64_t j = 0; j < n; ++j)
-                        sum += exp(a[j] - amax) * (1.0 + 0.5 * (double)d + a[j]);
+                    for (int64_t j = 0; j < n; ++j) {
+                        double factor = 1.0 + 0.5 * (double)d + a[j];
+                        if (laplace == 2) factor = fabs(factor);
+                        sum += exp(a[j] - amax) * factor;
+                    }
                     dens[i] = sum * exp(amax + lognorm);
                 }
             }
@@ -165,4 +169,11 @@ int sdkde_oracle_eval_laplace(const double *X, int64_t n, const double *Q, int64
                               double h, double *dens)
 {
     return eval_impl(X, n, Q, m, d, h, NULL, dens, 1);
+}
+
+/* Same sum with |1 + d/2 - r^2/2h^2| in place of the signed factor (a tolerance scale, not an estimator). */
+int sdkde_oracle_eval_laplace_abs(const double *X, int64_t n, const double *Q, int64_t m, int32_t d,
+                                  double h, double *dens)
+{
+    return eval_impl(X, n, Q, m, d, h, NULL, dens, 2);
 }

@@ -41,11 +41,12 @@ def load() -> ctypes.CDLL:
     lib.sdkde_score.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_debias.argtypes = [c_fp, c_fp, i64, i32, f64, c_fp, c_fp]
     lib.sdkde_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
+    lib.sdkde_eval_laplace.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_status_string.argtypes = [ctypes.c_int]
     lib.sdkde_status_string.restype = ctypes.c_char_p
     lib.sdkde_profile_enable.argtypes = [ctypes.c_int]
     lib.sdkde_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
-    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval",
+    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace",
                  "sdkde_profile_enable", "sdkde_profile_summary"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -156,6 +157,25 @@ def sdkde_eval(samples_sd, queries, h, density_out=None, log_density_out=None, w
         None if log_density_out is None else log_density_out.data_ptr(),
         ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
     return density_out, log_density_out
+
+
+def sdkde_eval_laplace(samples, queries, h, density_out=None, workspace=None, flags=SDKDE_PREC_FP32, stream=None):
+    """Laplace-corrected KDE of the (unshifted) samples at the queries; signed density [m]."""
+    x, q = _dev_f32(samples, "samples"), _dev_f32(queries, "queries")
+    n, d = x.shape
+    if q.dim() != 2 or q.shape[1] != d:
+        raise ValueError("queries must be [m, d]")
+    m = q.shape[0]
+    if density_out is None:
+        density_out = torch.empty(m, dtype=torch.float32, device=x.device)
+    _dev_f32(density_out, "density_out")
+    if density_out.numel() != m:
+        raise ValueError("density_out must have m elements")
+    ws = _workspace(workspace, n, m, d, x.device)
+    _check("sdkde_eval_laplace", load().sdkde_eval_laplace(
+        x.data_ptr(), n, q.data_ptr(), m, d, float(h), density_out.data_ptr(), ws.data_ptr(), ws.numel(), flags,
+        _stream_handle(stream)))
+    return density_out
 
 
 def sdkde_profile_enable(on: bool) -> None:

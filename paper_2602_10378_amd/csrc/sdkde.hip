@@ -32,6 +32,15 @@ constexpr int kMeanBlocks = 128;
 constexpr int kFlushTiles = 64;         // sample tiles between folds of the running sums (power of two)
 constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3, MFMA path above
 
+// What a pair kernel accumulates.
+enum PairKind {
+    kScoreSelf = 0,     // D and T at the samples themselves (own sample tiles skipped)
+    kScorePoints = 1,   // D and T at separate points
+    kEval = 2,          // D only (Gaussian KDE)
+    kEvalLaplace = 3    // sum of phi * (1 + d/2 - r^2/2h^2) (Laplace-corrected KDE; signed)
+};
+constexpr float kLn2 = 0.693147180559945309f;
+
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
 
 // ------------------------------------------------------------------------------------------
@@ -178,13 +187,16 @@ __device__ __forceinline__ void store_partials(float* __restrict__ part_t, float
     }
 }
 
-template <int KB, int NI, bool SCORE, bool SELF>
+template <int KB, int NI, int KIND>
 __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const float* __restrict__ ps, const float* __restrict__ pn, const float* __restrict__ xs,
     const float* __restrict__ xt, const float* __restrict__ xn, float* __restrict__ part_t,
-    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad)
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0)
 {
     static_assert(NI >= 2 && NI % 2 == 0, "the software pipeline alternates two accumulator sets");
+    constexpr bool SCORE = KIND == kScoreSelf || KIND == kScorePoints;
+    constexpr bool SELF = KIND == kScoreSelf;
+    constexpr bool LAPLACE = KIND == kEvalLaplace;
     constexpr int DP = KB * 16;
     constexpr int NM = 4 * KB;                 // MFMAs per contraction and tile
     constexpr int KT = SCORE ? KB : 1;
@@ -307,8 +319,19 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                 phi.y = __builtin_amdgcn_exp2f(c.y);
                 phi.z = __builtin_amdgcn_exp2f(c.z);
                 phi.w = __builtin_amdgcn_exp2f(c.w);
+                if (LAPLACE) {
+                    // c is the base-2 exponent -r^2/(2h^2) log2(e), so the Laplace factor
+                    // 1 + d/2 - r^2/(2h^2) is laplace_c0 + c ln 2 (Laplace-corrected KDE section).
+                    float acc = dacc[t];
+                    acc = fmaf(phi.x, fmaf(c.x, kLn2, laplace_c0), acc);
+                    acc = fmaf(phi.y, fmaf(c.y, kLn2, laplace_c0), acc);
+                    acc = fmaf(phi.z, fmaf(c.z, kLn2, laplace_c0), acc);
+                    acc = fmaf(phi.w, fmaf(c.w, kLn2, laplace_c0), acc);
+                    dacc[t] = acc;
+                } else {
+                    dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
+                }
                 c = (wrap2 ? nxt.nj : cur.nj) + nin;             // accumulator init of pair u+2
-                dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
                 __builtin_amdgcn_sched_barrier(0);
 
                 if (SCORE) {
@@ -424,11 +447,13 @@ __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
 // numerator N_i = sum_j phi_ij (x~_j - p~_i).  Same grid decomposition as the MFMA kernel with
 // row blocks of kBlock*R rows and "tiles" of 16 samples.
 // ------------------------------------------------------------------------------------------
-template <int D, int R, bool SCORE>
+template <int D, int R, int KIND>
 __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
     const float* __restrict__ ps, const float* __restrict__ xs, float* __restrict__ part_t,
-    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad)
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0)
 {
+    constexpr bool SCORE = KIND == kScoreSelf || KIND == kScorePoints;
+    constexpr bool LAPLACE = KIND == kEvalLaplace;
     const int split = blockIdx.x % nsplit;
     const int64_t row_block = blockIdx.x / nsplit;
     const int64_t row0 = row_block * (kBlock * R) + threadIdx.x;
@@ -462,7 +487,8 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
                     r2 = fmaf(diff[k], diff[k], r2);
                 }
                 float phi = __builtin_amdgcn_exp2f(-r2);
-                dacc[q] += phi;
+                if (LAPLACE) dacc[q] = fmaf(phi, fmaf(-r2, kLn2, laplace_c0), dacc[q]);   // factor 1 + d/2 - r^2/2h^2
+                else dacc[q] += phi;
                 if (SCORE) {
 #pragma unroll
                     for (int k = 0; k < D; ++k) nacc[q][k] = fmaf(phi, diff[k], nacc[q][k]);
@@ -515,8 +541,9 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
 }
 
 // log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
+// signed != 0 (Laplace-corrected sum, which may be negative): density = sum * exp(lognorm) only.
 __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __restrict__ part_d, int nsplit,
-                                                               int64_t m, int64_t m_pad, double lognorm,
+                                                               int64_t m, int64_t m_pad, double lognorm, int is_signed,
                                                                float* __restrict__ density,
                                                                float* __restrict__ log_density)
 {
@@ -524,6 +551,10 @@ __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __re
     if (i >= m) return;
     float dsum = 0.0f;
     for (int s = 0; s < nsplit; ++s) dsum += part_d[(int64_t)s * m_pad + i];
+    if (is_signed) {
+        if (density) density[i] = (float)((double)dsum * exp(lognorm));
+        return;
+    }
     double lp = log((double)dsum) + lognorm;      // -inf when dsum == 0
     if (log_density) log_density[i] = (float)lp;
     if (density) density[i] = (float)exp(lp);
@@ -673,25 +704,26 @@ struct Profile {
         if ((call) != hipSuccess) return SDKDE_EDEVICE;   \
     } while (0)
 
-template <bool SCORE, bool SELF>
+template <int KIND>
 int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
 {
     const dim3 grid((unsigned)(p.row_blocks * p.nsplit)), block(kBlock);
     if ((int64_t)p.row_blocks * p.nsplit > 0x7fffffffLL) return SDKDE_EUNSUPPORTED;
+    const float laplace_c0 = 1.0f + 0.5f * (float)p.d;
     // Host-side shape check: every row the grid touches exists in the padded arrays.
     if (p.row_blocks * p.rows_per_block > p.m_pad || (int64_t)p.ntiles * kTile > p.n_pad) return SDKDE_EINVAL;
 
 #define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                               \
     do {                                                                                                          \
-        hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, SCORE, SELF>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt, \
-                           w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad);             \
-        if constexpr (SCORE && SELF)                                                                              \
+        hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, KIND>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt, w.xn,  \
+                           w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0);       \
+        if constexpr (KIND == kScoreSelf)                                                                         \
             hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_>), dim3((unsigned)p.row_blocks), block, 0, st, w.xs,    \
                                w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                      \
     } while (0)
 #define SDKDE_LAUNCH_THIN(D_, R_)                                                                  \
-    hipLaunchKernelGGL((pair_thin_kernel<D_, R_, SCORE>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
-                       w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad)
+    hipLaunchKernelGGL((pair_thin_kernel<D_, R_, KIND>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
+                       w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0)
 #define SDKDE_CASE_NI(KB_, NI_) \
     case NI_: SDKDE_LAUNCH_MFMA(KB_, NI_); break;
 
@@ -786,6 +818,39 @@ int profile_mark(int which, int edge, hipStream_t st)
     return SDKDE_OK;
 }
 
+// Shared body of sdkde_eval and sdkde_eval_laplace.
+int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
+              float* density_out, float* log_density_out, void* workspace, size_t workspace_bytes, uint32_t flags,
+              void* stream, bool laplace)
+{
+    int rc = check_common(samples, n, m, d, h, flags);
+    if (rc != SDKDE_OK) return rc;
+    if (m == 0) return SDKDE_OK;
+    if (!queries || (!density_out && !log_density_out)) return SDKDE_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+
+    const Plan p = make_plan(n, m, d, false);
+    const Workspace w = layout(p, false, true, workspace);
+    if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
+    if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, nullptr, w.xn, kPadCoord, st)) != SDKDE_OK)
+        return rc;
+    if ((rc = launch_prep(p, queries, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, st)) != SDKDE_OK) return rc;
+
+    if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
+    rc = laplace ? launch_pair<kEvalLaplace>(p, w, st) : launch_pair<kEval>(p, w, st);
+    if (rc != SDKDE_OK) return rc;
+    if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
+
+    const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
+    hipLaunchKernelGGL(eval_epilogue_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
+                       p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0, density_out, log_density_out);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -833,7 +898,7 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
         return rc;
 
     if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
-    rc = self ? launch_pair<true, true>(p, w, st) : launch_pair<true, false>(p, w, st);
+    rc = self ? launch_pair<kScoreSelf>(p, w, st) : launch_pair<kScorePoints>(p, w, st);
     if (rc != SDKDE_OK) return rc;
     if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
 
@@ -860,31 +925,15 @@ int sdkde_eval(const float* samples_sd, int64_t n, const float* queries, int64_t
                float* density_out, float* log_density_out, void* workspace, size_t workspace_bytes, uint32_t flags,
                void* stream)
 {
-    int rc = check_common(samples_sd, n, m, d, h, flags);
-    if (rc != SDKDE_OK) return rc;
-    if (m == 0) return SDKDE_OK;
-    if (!queries || (!density_out && !log_density_out)) return SDKDE_EINVAL;
-    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+    return eval_impl(samples_sd, n, queries, m, d, h, density_out, log_density_out, workspace, workspace_bytes, flags,
+                     stream, false);
+}
 
-    const Plan p = make_plan(n, m, d, false);
-    const Workspace w = layout(p, false, true, workspace);
-    if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-
-    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
-    if ((rc = launch_mean(samples_sd, n, d, w, st)) != SDKDE_OK) return rc;
-    if ((rc = launch_prep(p, samples_sd, n, p.n_pad, (float)a, w, w.xs, nullptr, w.xn, kPadCoord, st)) != SDKDE_OK)
-        return rc;
-    if ((rc = launch_prep(p, queries, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, st)) != SDKDE_OK) return rc;
-
-    if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
-    if ((rc = launch_pair<false, false>(p, w, st)) != SDKDE_OK) return rc;
-    if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
-
-    const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
-    hipLaunchKernelGGL(eval_epilogue_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
-                       p.nsplit, m, p.m_pad, lognorm, density_out, log_density_out);
-    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+int sdkde_eval_laplace(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
+                       float* density_out, void* workspace, size_t workspace_bytes, uint32_t flags, void* stream)
+{
+    return eval_impl(samples, n, queries, m, d, h, density_out, nullptr, workspace, workspace_bytes, flags, stream,
+                     true);
 }
 
 const char* sdkde_status_string(int status)

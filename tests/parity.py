@@ -61,3 +61,14 @@ def assert_shifted_close(x_sd_gpu, x_sd_ref, s_ref, h, what=""):
     worst = float(np.max(err / allow))
     assert worst <= 1.0, f"{what}: shifted-sample error {worst:.3g}x the allowance"
     return worst
+
+
+def assert_laplace_close(p_gpu, p_ref, p_abs_ref, what=""):
+    """Signed Laplace-corrected density: |error| <= 1e-3 * max(|p_ref|, 1e-3 * p_abs_ref), where
+    p_abs_ref sums the magnitudes of the terms that cancel in p_ref."""
+    p_gpu = np.asarray(p_gpu, dtype=np.float64)
+    big = p_abs_ref >= 1e-30
+    allow = TOL * np.maximum(np.abs(p_ref[big]), 1e-3 * p_abs_ref[big])
+    worst = float(np.max(np.abs(p_gpu[big] - p_ref[big]) / allow)) if big.any() else 0.0
+    assert worst <= 1.0, f"{what}: Laplace density error {worst:.3g}x the allowance"
+    return worst

@@ -5,7 +5,8 @@ import pytest
 
 import oracle
 import sdkde_inputs
-from parity import assert_density_close, assert_log_density_close, assert_score_close, assert_shifted_close
+from parity import (assert_density_close, assert_laplace_close, assert_log_density_close, assert_score_close,
+                    assert_shifted_close)
 
 pytestmark = pytest.mark.gpu
 
@@ -97,6 +98,20 @@ def test_score_at_separate_points(lib, d):
     x, q, h = _mixture(1300, 257, d, 21)
     got = P.sdkde_score(torch.from_numpy(x).cuda(), h, points=torch.from_numpy(q).cuda()).cpu().numpy()
     assert_score_close(got, oracle.score(x, h, points=q), f"points d={d}")
+
+
+@pytest.mark.parametrize("n,m,d,seed", [(3000, 777, 1, 0), (1500, 300, 2, 3), (4096, 1024, 16, 0), (1000, 333, 16, 1),
+                                        (1200, 200, 5, 6), (2048, 512, 64, 10), (17, 9, 16, 2)])
+def test_laplace_corrected_kde_matches_oracle(lib, n, m, d, seed):
+    P, torch = lib
+    print(f"laplace n={n} m={m} d={d}", flush=True)
+    x, q, h = _mixture(n, m, d, seed)
+    got = P.sdkde_eval_laplace(torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda(), h).cpu().numpy()
+    ref = oracle.eval_laplace_density(x, q, h)
+    mag = oracle.eval_laplace_abs_density(x, q, h)
+    assert_laplace_close(got, ref, mag, f"laplace n={n} d={d}")
+    if d <= 16:
+        assert (got < 0).any() or (ref >= 0).all()     # negative tails survive where the oracle has them
 
 
 def test_single_sample_closed_form(lib):

@@ -83,6 +83,7 @@ def test_debias_is_x_plus_half_h2_score():
 
 def test_1d_density_integrates_to_one_with_right_moments():
     x, _, h = sdkde_inputs.mixture_1d(400, 8, seed=3)
+    x = x.astype(np.float64)
     s = oracle.score(x, h)
     x_sd = oracle.debias(x, s, h)
     lo, hi = x_sd.min() - 10 * h, x_sd.max() + 10 * h
@@ -241,6 +242,28 @@ def test_laplace_corrected_matches_definition(cloud):
         e[kk] = eps
         lap += (oracle.eval_density(x, q + e, h) - 2 * p0 + oracle.eval_density(x, q - e, h)) / eps**2
     np.testing.assert_allclose(oracle.eval_laplace_density(x, q, h), p0 - 0.5 * h * h * lap, rtol=2e-5, atol=1e-12 * p0.max())
+
+
+def test_laplace_abs_scale_bounds_signed_sum(cloud):
+    x, q, h = cloud
+    signed = oracle.eval_laplace_density(x, q, h)
+    mag = oracle.eval_laplace_abs_density(x, q, h)
+    assert np.all(mag >= np.abs(signed) * (1 - 1e-12))
+    d = x.shape[1]
+    r2 = ((q - x[:1]) ** 2).sum(1)
+    k = np.exp(-r2 / (2 * h * h)) / ((2 * math.pi) ** (d / 2) * h**d)
+    np.testing.assert_allclose(oracle.eval_laplace_abs_density(x[:1], q, h), k * np.abs(1 + d / 2 - r2 / (2 * h * h)), rtol=1e-12)
+
+
+def test_laplace_integrates_to_one_1d():
+    # the correction term -(h^2/2) Laplacian(K_h) integrates to zero, so p_LC keeps unit mass
+    x, _, h = sdkde_inputs.mixture_1d(300, 4, seed=5)
+    x = x.astype(np.float64)        # keep the grid arithmetic in double
+    grid = np.linspace(x.min() - 12 * h, x.max() + 12 * h, 30001)
+    p = oracle.eval_laplace_density(x, grid.reshape(-1, 1), h)
+    dx = grid[1] - grid[0]
+    assert float(np.sum((p[1:] + p[:-1]) * 0.5) * dx) == pytest.approx(1.0, abs=1e-9)
+    assert p.min() < 0.0          # and it does go negative in the tails, as the paper notes
 
 
 def test_gaussian_data_score_is_roughly_linear():
