@@ -133,12 +133,15 @@ def main():
                            "kernel": "pair_mfma_kernel (score)", "launch_ms": score_avg_ms,
                            "flops_per_launch": score_flops}
     else:
-        # thin-d path: VALU/transcendental bound; 5 lane-ops (4 VALU + 1 exp) per score pair
-        ops = 5.0 * float(n) * n
-        peak = 256 * 4 * 16 * 2.4e9 / 1e12      # lane-ops/s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
-        ach = ops / (score_avg_ms * 1e-3) / 1e12
-        out["roofline"] = {"bound": "alu", "achieved": ach, "peak": peak, "unit": "Tlane-op/s", "frac": ach / peak,
-                           "traffic": None, "kernel": "pair_thin_kernel (score)", "launch_ms": score_avg_ms}
+        # thin-d path (Appendix A): VALU-issue bound.  Per score pair: d subs + d FMAs (r^2) + 1 add (D) + d FMAs
+        # (numerator) + one v_exp_f32, which issues at half rate (2 slots).  Peak = 256 CUs x 4 SIMDs x 16 lanes x
+        # 2.4 GHz = 39.3 T lane-slots/s (fp32 VALU without packed math; 78.6 TFLOP/s counting an FMA as 2 flops).
+        slots = (3 * d + 1 + 2) * float(n) * n
+        peak = 256 * 4 * 16 * 2.4e9 / 1e12
+        ach = slots / (score_avg_ms * 1e-3) / 1e12
+        out["roofline"] = {"bound": "alu", "achieved": ach, "peak": peak, "unit": "T lane-slots/s", "frac": ach / peak,
+                           "traffic": None, "kernel": "pair_thin_kernel (score)", "launch_ms": score_avg_ms,
+                           "slots_per_pair": 3 * d + 3}
     if not args.no_cpu_baseline:
         base, s_rows = cpu_baseline(x, q, h)
         out["cpu_baseline"] = base
