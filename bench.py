@@ -65,6 +65,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the config's sample count (same distribution)")
     ap.add_argument("--m", type=int, default=None, help="override the config's query count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-modes", action="store_true", help="skip the separately reported fp16x2-input mode")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)")
@@ -87,10 +88,10 @@ def main():
     dens = torch.empty(m, dtype=torch.float32, device=dev)
     logd = torch.empty(m, dtype=torch.float32, device=dev)
 
-    def step():
-        P.sdkde_score(xd, h, out=s, workspace=ws)
+    def step(flags=P.SDKDE_PREC_FP32):
+        P.sdkde_score(xd, h, out=s, workspace=ws, flags=flags)
         P.sdkde_debias(xd, s, h, out=x_sd)
-        P.sdkde_eval(x_sd, qd, h, density_out=dens, log_density_out=logd, workspace=ws)
+        P.sdkde_eval(x_sd, qd, h, density_out=dens, log_density_out=logd, workspace=ws, flags=flags)
 
     for _ in range(args.warmup):
         step()
@@ -104,6 +105,30 @@ def main():
     score_launches, score_ms = P.sdkde_profile_summary(0)
     eval_launches, eval_ms = P.sdkde_profile_summary(1)
     P.sdkde_profile_enable(False)
+
+    s_fp32 = s.clone()
+    logd_fp32 = logd.clone()
+    other = None
+    if not args.no_other_modes and d > 3:
+        # Lower-precision-input mode, reported separately: same steps, same timing protocol.
+        step(P.SDKDE_PREC_FP16X2)
+        torch.cuda.synchronize()
+        P.sdkde_profile_enable(True)
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            step(P.SDKDE_PREC_FP16X2)
+        torch.cuda.synchronize()
+        dt16 = time.perf_counter() - t1
+        l16, ms16 = P.sdkde_profile_summary(0)
+        P.sdkde_profile_enable(False)
+        other = {"fp16x2_inputs": {
+            "value": (float(n) * n + float(m) * n) / (dt16 / args.steps), "unit": "pairs/s",
+            "ms_per_step": dt16 / args.steps * 1e3, "score_main_kernel_ms": ms16 / max(l16, 1),
+            "score_rel_frobenius_vs_fp32_path": float((s - s_fp32).norm() / s_fp32.norm()),
+            "max_abs_log_density_diff_vs_fp32_path": float((logd - logd_fp32).abs().max()),
+            "note": "cross-term inputs split into fp16 hi+lo on the fp16 matrix units, fp32 accumulate; "
+                    "error vs the oracle is measured in tests/test_gpu_full_size.py"}}
+        s.copy_(s_fp32)
 
     pairs = float(n) * n + float(m) * n
     ms_per_step = dt / args.steps * 1e3
@@ -142,6 +167,8 @@ def main():
         out["roofline"] = {"bound": "alu", "achieved": ach, "peak": peak, "unit": "T lane-slots/s", "frac": ach / peak,
                            "traffic": None, "kernel": "pair_thin_kernel (score)", "launch_ms": score_avg_ms,
                            "slots_per_pair": 3 * d + 3}
+    if other:
+        out["other_modes"] = other
     if not args.no_cpu_baseline:
         base, s_rows = cpu_baseline(x, q, h)
         out["cpu_baseline"] = base

@@ -13,7 +13,8 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is only
  *    enqueued; no call synchronises with the host, and no call allocates device memory.
  *  - h is passed as double so that the derived constants are formed in double and rounded
- *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation).
+ *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation) unless
+ *    `flags` selects another input mode.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
  *    arguments give bit-identical outputs.
  *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
@@ -39,7 +40,12 @@ enum {
 
 enum {
     SDKDE_MAX_D = 128,
-    SDKDE_PREC_FP32 = 0     /* flags bits 0-3: precision mode; only fp32 is defined */
+    /* flags: precision mode of the distance cross term (the Gram-matrix tile of the Method section) */
+    SDKDE_PREC_FP32 = 0,    /* fp32 MFMA inputs, fp32 accumulate: the reference path */
+    SDKDE_PREC_FP16X2 = 1   /* each input split into two fp16 halves (hi + lo, ~22 mantissa bits) and
+                               multiplied on the fp16 matrix units with fp32 accumulate; Phi X, exp and all
+                               sums stay fp32.  A lower-precision-input mode: its error is reported
+                               separately.  Ignored (fp32 VALU) for d <= 3. */
 };
 
 /*

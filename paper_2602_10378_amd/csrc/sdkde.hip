@@ -20,6 +20,7 @@
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kWave = 64;
 constexpr int kBlock = 256;            // 4 waves per workgroup
@@ -82,22 +83,34 @@ __global__ void mean_final_kernel(const double* __restrict__ partial, int blocks
 // One thread per padded row.  Writes xs[row][dp] = a (x - mean) (0 in padding columns and rows),
 // nrm[row] = -|xs[row]|^2 (kPadNorm for padding rows) and, if xt != nullptr, the same values in
 // 16-sample blocks transposed: xt[row/16][col][row%16].
+// split_half != 0 (fp16x2 input mode): xs holds, per 16-column block, 16 fp16 "hi" values followed
+// by 16 fp16 "lo" values with hi + lo = the fp32 coordinate to ~22 mantissa bits (same bytes per
+// row as fp32); the norm is then taken of hi + lo so that it matches what the MFMA multiplies.
 __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(const float* __restrict__ x, int64_t n, int d,
                                                            int dp, int64_t rows_pad,
                                                            const float* __restrict__ mean, float a,
                                                            float* __restrict__ xs, float* __restrict__ xt,
-                                                           float* __restrict__ nrm)
+                                                           float* __restrict__ nrm, int split_half)
 {
     int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (row >= rows_pad) return;
     const bool live = row < n;
     double acc = 0.0;
     float* xt_row = xt ? xt + (row / kTile) * (int64_t)dp * kTile + (row % kTile) : nullptr;
+    _Float16* xh = reinterpret_cast<_Float16*>(xs) + row * 2 * dp;
     for (int c = 0; c < dp; ++c) {
         float v = 0.0f;
         if (live && c < d) v = a * (x[row * d + c] - mean[c]);
-        xs[row * dp + c] = v;
         if (xt_row) xt_row[(int64_t)c * kTile] = v;
+        if (split_half) {
+            const _Float16 hi = (_Float16)v;
+            const _Float16 lo = (_Float16)(v - (float)hi);
+            xh[(c / 16) * 32 + (c % 16)] = hi;
+            xh[(c / 16) * 32 + 16 + (c % 16)] = lo;
+            v = (float)hi + (float)lo;
+        } else {
+            xs[row * dp + c] = v;
+        }
         acc += (double)v * (double)v;
     }
     nrm[row] = live ? -(float)acc : kPadNorm;
@@ -145,24 +158,56 @@ __global__ __launch_bounds__(kBlock) void prep_thin_kernel(const float* __restri
 //   ps, pn : m_pad rows (multiple of kRowPad >= RB);  xs, xt, xn : ntiles*16 rows.
 // ------------------------------------------------------------------------------------------
 
-// Row-tile operands of one wave: B operand 2 * p~ (lane (r, g) holds coordinates 16kb + 4g .. +3
-// of row r) and -|p~|^2 for NI row tiles starting at row0.
-template <int KB, int NI>
-__device__ __forceinline__ void load_row_tiles(const float* __restrict__ ps, const float* __restrict__ pn,
-                                               int64_t row0, int r, int g, f32x4 (&b)[NI][KB], float (&ni)[NI])
-{
-    constexpr int DP = KB * 16;
+// Row-tile operands of one wave for NI row tiles starting at row0: -|p~|^2 and the B operand 2 * p~.
+// fp32 inputs: lane (r, g) holds coordinates 16kb + 4g .. +3 of row r (b[t][kb]).
+// fp16x2 inputs: two K = 32 operands per 16-column block, bh[t][kb][0] = [hi | hi] and
+// bh[t][kb][1] = [lo | lo]; lane (r, g) holds elements 8g .. 8g+7 of that K axis, i.e. halves
+// 8(g&1) .. +7 of the hi (resp. lo) part.  Against the streamed A operand [hi | lo] the two MFMAs
+// sum hi*hi + lo*hi + hi*lo + lo*lo = the full product.
+template <int KB, int NI, int PREC>
+struct RowTiles {
+    f32x4 b[PREC == SDKDE_PREC_FP32 ? NI : 1][KB];
+    f16x8 bh[PREC == SDKDE_PREC_FP16X2 ? NI : 1][KB][2];
+    float ni[NI];
+
+    __device__ __forceinline__ void load(const float* __restrict__ ps, const float* __restrict__ pn, int64_t row0,
+                                         int r, int g)
+    {
+        constexpr int DP = KB * 16;
 #pragma unroll
-    for (int t = 0; t < NI; ++t) {
-        const int64_t row = row0 + t * kTile + r;
+        for (int t = 0; t < NI; ++t) {
+            const int64_t row = row0 + t * kTile + r;
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            f32x4 v = *reinterpret_cast<const f32x4*>(ps + row * DP + kb * 16 + g * 4);
-            b[t][kb] = v * 2.0f;
+            for (int kb = 0; kb < KB; ++kb) {
+                if (PREC == SDKDE_PREC_FP32) {
+                    f32x4 v = *reinterpret_cast<const f32x4*>(ps + row * DP + kb * 16 + g * 4);
+                    b[t][kb] = v * 2.0f;
+                } else {
+                    const _Float16* ph = reinterpret_cast<const _Float16*>(ps) + row * 2 * DP + kb * 32 + (g & 1) * 8;
+                    bh[t][kb][0] = *reinterpret_cast<const f16x8*>(ph) * (_Float16)2;
+                    bh[t][kb][1] = *reinterpret_cast<const f16x8*>(ph + 16) * (_Float16)2;
+                }
+            }
+            ni[t] = pn[row];
         }
-        ni[t] = pn[row];
     }
-}
+
+    // c += (16 samples x 16-column block kb) * (row tile t)^T; a = the lane's 16 bytes of the streamed operand.
+    __device__ __forceinline__ f32x4 cross(int t, int kb, const f32x4& a, f32x4 c) const
+    {
+        if (PREC == SDKDE_PREC_FP32) {
+            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b[t][kb].x, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b[t][kb].y, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b[t][kb].z, c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b[t][kb].w, c, 0, 0, 0);
+        } else {
+            const f16x8 ah = __builtin_bit_cast(f16x8, a);
+            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[t][kb][0], c, 0, 0, 0);
+            c = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[t][kb][1], c, 0, 0, 0);
+        }
+        return c;
+    }
+};
 
 // Writes one wave's partial sums: T^T accumulator (lane (r, g), register v) = coordinate
 // 16mb + 4g + v of row r; D needs the sum over the four lane groups g.
@@ -187,7 +232,7 @@ __device__ __forceinline__ void store_partials(float* __restrict__ part_t, float
     }
 }
 
-template <int KB, int NI, int KIND>
+template <int KB, int NI, int KIND, int PREC>
 __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const float* __restrict__ ps, const float* __restrict__ pn, const float* __restrict__ xs,
     const float* __restrict__ xt, const float* __restrict__ xn, float* __restrict__ part_t,
@@ -201,15 +246,15 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     constexpr int NM = 4 * KB;                 // MFMAs per contraction and tile
     constexpr int KT = SCORE ? KB : 1;
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);    // wave-uniform by construction
     const int r = lane & 15, g = lane >> 4;
     const int split = blockIdx.x % nsplit;
     const int64_t row_block = blockIdx.x / nsplit;
     const int64_t row0 = (row_block * kWavesPerBlock + wave) * (NI * kTile);
 
-    f32x4 b[NI][KB];
-    float ni[NI];
-    load_row_tiles<KB, NI>(ps, pn, row0, r, g, b, ni);
+    RowTiles<KB, NI, PREC> rows;
+    rows.load(ps, pn, row0, r, g);
+    const float (&ni)[NI] = rows.ni;
 
     // Two-level accumulation: the running sums (tacc, dacc) are folded into (tsum, dsum) every
     // kFlushTiles sample tiles, so no fp32 accumulator sees more than a short chain of additions
@@ -284,8 +329,7 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         load_nj(s_begin, set_a);
         creg[0] = set_a.nj + ni[0];
 #pragma unroll
-        for (int i = 0; i < NM; ++i)
-            creg[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(set_a.a1[i / 4][i % 4], b[0][i / 4][i % 4], creg[0], 0, 0, 0);
+        for (int kb = 0; kb < KB; ++kb) creg[0] = rows.cross(0, kb, set_a.a1[kb], creg[0]);
         creg[1] = set_a.nj + ni[1];
         load_a1(s_begin + 1, set_b);
         load_nj(s_begin + 1, set_b);
@@ -307,11 +351,8 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
-                for (int i = 0; i < NM; ++i) {
-                    const int kb = i / 4, kk = i % 4;
-                    const float av = wrap1 ? nxt.a1[kb][kk] : cur.a1[kb][kk];
-                    creg[slot ^ 1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, b[(t + 1) % NI][kb][kk], creg[slot ^ 1], 0, 0, 0);
-                }
+                for (int kb = 0; kb < KB; ++kb)
+                    creg[slot ^ 1] = rows.cross((t + 1) % NI, kb, wrap1 ? nxt.a1[kb] : cur.a1[kb], creg[slot ^ 1]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (t == NI - 2) load_a1(jt + 2, cur);    // cur.a1 was last read by the MFMAs above
 
@@ -377,21 +418,20 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 // the sums into partial slot `slot` (one past the splits of pair_mfma_kernel).  Same operand
 // layouts as above; a plain loop, since this is NI*16 pairs per row out of n.
 // Grid: one workgroup per row block, as in the main kernel.
-template <int KB, int NI>
+template <int KB, int NI, int PREC>
 __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
     const float* __restrict__ xs, const float* __restrict__ xt, const float* __restrict__ xn,
     float* __restrict__ part_t, float* __restrict__ part_d, int ntiles, int slot, int64_t m_pad)
 {
     constexpr int DP = KB * 16;
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);    // wave-uniform by construction
     const int r = lane & 15, g = lane >> 4;
     const int64_t row0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * (NI * kTile);
     const int dt0 = (int)(row0 / kTile);
 
-    f32x4 b[NI][KB];
-    float ni[NI];
-    load_row_tiles<KB, NI>(xs, xn, row0, r, g, b, ni);
+    RowTiles<KB, NI, PREC> rows;
+    rows.load(xs, xn, row0, r, g);
     f32x4 tsum[NI][KB];
     float dsum[NI];
 #pragma unroll
@@ -415,12 +455,9 @@ __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
         const f32x4 nj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
 #pragma unroll
         for (int t = 0; t < NI; ++t) {
-            f32x4 c = nj + ni[t];
+            f32x4 c = nj + rows.ni[t];
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[kb][kk], b[t][kb][kk], c, 0, 0, 0);
+            for (int kb = 0; kb < KB; ++kb) c = rows.cross(t, kb, a1[kb], c);
             f32x4 phi;
             // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
             const bool own = t == dt;
@@ -511,6 +548,7 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
 // Split reduction + epilogues (fixed summation order over splits: deterministic).
 // ------------------------------------------------------------------------------------------
 
+// ps_split_half: p~ is stored as fp16 hi/lo pairs (fp16x2 input mode) and is rebuilt as hi + lo.
 // mode 0 (MFMA path, separate points): score = (T/D - p~) * inv_ah2            (T = Phi X regrouping)
 // mode 1 (thin path):                   score = (N/D) * inv_ah2                (direct-form numerator)
 // mode 2 (MFMA path, at the samples):   score = (T' - p~ D') / (D' + 1) * inv_ah2
@@ -518,7 +556,7 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
 // inv_ah2 = 1 / (a h^2) undoes the coordinate scaling.  D == 0 gives 0.
 __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
     const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
-    int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, float inv_ah2,
+    int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, int ps_split_half, float inv_ah2,
     float* __restrict__ score)
 {
     int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
@@ -530,12 +568,21 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
         tsum += part_t[((int64_t)s * m_pad + i) * dp + c];
         dsum += part_d[(int64_t)s * m_pad + i];
     }
+    float pc = 0.0f;                       // p~_i[c]
+    if (mode != 1) {
+        if (ps_split_half) {
+            const _Float16* ph = reinterpret_cast<const _Float16*>(ps) + i * 2 * dp + (c / 16) * 32 + (c % 16);
+            pc = (float)ph[0] + (float)ph[16];
+        } else {
+            pc = ps[i * dp + c];
+        }
+    }
     float out = 0.0f;
     if (mode == 2) {
-        out = fmaf(-ps[i * dp + c], dsum, tsum) / (dsum + 1.0f) * inv_ah2;
+        out = fmaf(-pc, dsum, tsum) / (dsum + 1.0f) * inv_ah2;
     } else if (dsum > 0.0f) {
         float ratio = tsum / dsum;
-        out = (mode == 1 ? ratio : ratio - ps[i * dp + c]) * inv_ah2;
+        out = (mode == 1 ? ratio : ratio - pc) * inv_ah2;
     }
     score[idx] = out;
 }
@@ -704,7 +751,7 @@ struct Profile {
         if ((call) != hipSuccess) return SDKDE_EDEVICE;   \
     } while (0)
 
-template <int KIND>
+template <int KIND, int PREC>
 int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
 {
     const dim3 grid((unsigned)(p.row_blocks * p.nsplit)), block(kBlock);
@@ -715,11 +762,11 @@ int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
 
 #define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                               \
     do {                                                                                                          \
-        hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, KIND>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt, w.xn,  \
-                           w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0);       \
+        hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, KIND, PREC>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt,  \
+                           w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0); \
         if constexpr (KIND == kScoreSelf)                                                                         \
-            hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_>), dim3((unsigned)p.row_blocks), block, 0, st, w.xs,    \
-                               w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                      \
+            hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_, PREC>), dim3((unsigned)p.row_blocks), block, 0, st,   \
+                               w.xs, w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                \
     } while (0)
 #define SDKDE_LAUNCH_THIN(D_, R_)                                                                  \
     hipLaunchKernelGGL((pair_thin_kernel<D_, R_, KIND>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
@@ -777,6 +824,14 @@ int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
+template <int KIND>
+int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, hipStream_t st)
+{
+    // the thin-d path has no matrix inputs: it runs the same fp32 VALU code for every mode
+    if ((flags & 15u) == SDKDE_PREC_FP16X2 && !p.thin) return launch_pair<KIND, SDKDE_PREC_FP16X2>(p, w, st);
+    return launch_pair<KIND, SDKDE_PREC_FP32>(p, w, st);
+}
+
 // Column means of src[rows][d] into w.mean.
 int launch_mean(const float* src, int64_t rows, int d, const Workspace& w, hipStream_t st)
 {
@@ -788,21 +843,21 @@ int launch_mean(const float* src, int64_t rows, int d, const Workspace& w, hipSt
 
 // Centre/scale/pad `src` into (dst, dst_t, dst_n) with rows_pad rows.
 int launch_prep(const Plan& p, const float* src, int64_t rows, int64_t rows_pad, float a, const Workspace& w,
-                float* dst, float* dst_t, float* dst_n, float pad_value, hipStream_t st)
+                float* dst, float* dst_t, float* dst_n, float pad_value, uint32_t flags, hipStream_t st)
 {
     const dim3 grid((unsigned)((rows_pad + kBlock - 1) / kBlock)), block(kBlock);
     if (p.thin)
         hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, src, rows, p.d, rows_pad, w.mean, a, pad_value, dst);
     else
         hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, src, rows, p.d, p.dp, rows_pad, w.mean, a, dst,
-                           dst_t, dst_n);
+                           dst_t, dst_n, (flags & 15u) == SDKDE_PREC_FP16X2 ? 1 : 0);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
 int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h, uint32_t flags)
 {
     if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
-    if (d > SDKDE_MAX_D || flags != SDKDE_PREC_FP32) return SDKDE_EUNSUPPORTED;
+    if (d > SDKDE_MAX_D || (flags != SDKDE_PREC_FP32 && flags != SDKDE_PREC_FP16X2)) return SDKDE_EUNSUPPORTED;
     if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
     return SDKDE_OK;
 }
@@ -836,12 +891,12 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
 
     const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
     if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
-    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, nullptr, w.xn, kPadCoord, st)) != SDKDE_OK)
+    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, nullptr, w.xn, kPadCoord, flags, st)) != SDKDE_OK)
         return rc;
-    if ((rc = launch_prep(p, queries, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_prep(p, queries, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, flags, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
-    rc = laplace ? launch_pair<kEvalLaplace>(p, w, st) : launch_pair<kEval>(p, w, st);
+    rc = laplace ? launch_pair_prec<kEvalLaplace>(p, w, flags, st) : launch_pair_prec<kEval>(p, w, flags, st);
     if (rc != SDKDE_OK) return rc;
     if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
 
@@ -892,13 +947,13 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     // When the points are the samples (m == n, so m_pad == n_pad), one prepared array serves
     // as both operands.
     if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
-    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, w.xt, w.xn, kPadCoord, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, w.xt, w.xn, kPadCoord, flags, st)) != SDKDE_OK) return rc;
     if (!self &&
-        (rc = launch_prep(p, points, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, st)) != SDKDE_OK)
+        (rc = launch_prep(p, points, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, flags, st)) != SDKDE_OK)
         return rc;
 
     if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
-    rc = self ? launch_pair<kScoreSelf>(p, w, st) : launch_pair<kScorePoints>(p, w, st);
+    rc = self ? launch_pair_prec<kScoreSelf>(p, w, flags, st) : launch_pair_prec<kScorePoints>(p, w, flags, st);
     if (rc != SDKDE_OK) return rc;
     if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
 
@@ -906,7 +961,8 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     const float inv_ah2 = (float)(1.0 / (a * h * h));
     hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
                        w.part_t, w.part_d, w.ps, p.nsplit + ((self && !p.thin) ? 1 : 0), m, p.m_pad, d, p.dp,
-                       p.thin ? 1 : (self ? 2 : 0), inv_ah2, score_out);
+                       p.thin ? 1 : (self ? 2 : 0), (!p.thin && (flags & 15u) == SDKDE_PREC_FP16X2) ? 1 : 0, inv_ah2,
+                       score_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
