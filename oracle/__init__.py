@@ -26,21 +26,31 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def _configure(lib):
+    dp = ctypes.POINTER(ctypes.c_double)
+    i64, i32, f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+    lib.sdkde_oracle_threads.restype = ctypes.c_int
+    lib.sdkde_oracle_score.argtypes = [dp, i64, dp, i64, i32, f64, dp]
+    lib.sdkde_oracle_debias.argtypes = [dp, dp, i64, i32, f64, dp]
+    lib.sdkde_oracle_eval.argtypes = [dp, i64, dp, i64, i32, f64, dp, dp]
+    lib.sdkde_oracle_eval_laplace.argtypes = [dp, i64, dp, i64, i32, f64, dp]
+    lib.sdkde_oracle_eval_laplace_abs.argtypes = [dp, i64, dp, i64, i32, f64, dp]
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
         build()
-        lib = ctypes.CDLL(_LIB)
-        dp = ctypes.POINTER(ctypes.c_double)
-        i64, i32, f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_double
-        lib.sdkde_oracle_threads.restype = ctypes.c_int
-        lib.sdkde_oracle_score.argtypes = [dp, i64, dp, i64, i32, f64, dp]
-        lib.sdkde_oracle_debias.argtypes = [dp, dp, i64, i32, f64, dp]
-        lib.sdkde_oracle_eval.argtypes = [dp, i64, dp, i64, i32, f64, dp, dp]
-        lib.sdkde_oracle_eval_laplace.argtypes = [dp, i64, dp, i64, i32, f64, dp]
-        lib.sdkde_oracle_eval_laplace_abs.argtypes = [dp, i64, dp, i64, i32, f64, dp]
-        _lib = lib
+        _lib = _configure(ctypes.CDLL(_LIB))
     return _lib
+
+
+def use_library(path):
+    """Test hook: route every call through another build of the oracle source (a deliberately
+    broken one, to check that the pins notice); path=None restores the real library."""
+    global _lib
+    _lib = None if path is None else _configure(ctypes.CDLL(path))
 
 
 def _f64(a):

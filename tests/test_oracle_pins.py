@@ -108,10 +108,14 @@ def test_2d_density_integrates_to_one():
 
 # ---------------------------------------------------------------- invariants
 
-@pytest.fixture(scope="module")
-def cloud():
+def make_cloud():
     x, q, h = sdkde_inputs.gaussian_mixture(300, 40, 5, components=3, seed=7)
     return x.astype(np.float64), q.astype(np.float64), h
+
+
+@pytest.fixture(scope="module")
+def cloud():
+    return make_cloud()
 
 
 def test_translation_invariance(cloud):
