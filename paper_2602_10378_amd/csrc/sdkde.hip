@@ -70,61 +70,111 @@ __global__ __launch_bounds__(kBlock) void mean_partial_kernel(const float* __res
     }
 }
 
-__global__ void mean_final_kernel(const double* __restrict__ partial, int blocks, int d, int64_t n,
-                                  float* __restrict__ mean)
+// Second stage of the column mean, done by every prep workgroup for itself (saves a launch):
+// sums the kMeanBlocks partials of each column in a fixed order, so all workgroups get the same
+// bits.  Result in smean[0 .. d); ends with a barrier.
+__device__ __forceinline__ void block_mean(const double* __restrict__ partial, int d, int64_t n, double* red,
+                                           float* smean)
 {
-    int c = threadIdx.x;
-    if (c >= d) return;
-    double s = 0.0;
-    for (int b = 0; b < blocks; ++b) s += partial[(int64_t)b * d + c];
-    mean[c] = (float)(s / (double)n);
+    const int slices = kBlock / d;                        // d <= 128, so >= 2
+    const int sl = threadIdx.x / d, c = threadIdx.x % d;
+    double acc = 0.0;
+    if (sl < slices)
+        for (int b = sl; b < kMeanBlocks; b += slices) acc += partial[(int64_t)b * d + c];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < d) {
+        double t = 0.0;
+        for (int q = 0; q < slices; ++q) t += red[q * d + threadIdx.x];
+        smean[threadIdx.x] = (float)(t / (double)n);
+    }
+    __syncthreads();
 }
 
-// One thread per padded row.  Writes xs[row][dp] = a (x - mean) (0 in padding columns and rows),
-// nrm[row] = -|xs[row]|^2 (kPadNorm for padding rows) and, if xt != nullptr, the same values in
-// 16-sample blocks transposed: xt[row/16][col][row%16].
-// split_half != 0 (fp16x2 input mode): xs holds, per 16-column block, 16 fp16 "hi" values followed
+// One array to prepare: src[rows][d] -> dst (rows_pad rows), optional blocked transpose dst_t, norms dst_n.
+struct PrepJob {
+    const float* src;
+    int64_t rows, rows_pad;
+    float* dst;
+    float* dst_t;
+    float* dst_n;
+    float pad_value;      // thin path only: coordinate value of padding rows
+};
+
+constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (two 16-sample tiles; 2 x 16.5 KiB of LDS)
+
+// Centre, scale and pad for the MFMA path.  A workgroup stages kPrepRows rows in LDS and writes
+//   dst[row][dp]   = a (x - mean), 0 in padding columns and rows (coalesced row writes),
+//   dst_t[row/16][col][row%16] = the same values with each 16-sample tile transposed (if dst_t),
+//   dst_n[row]     = -|dst[row]|^2 in double, rounded once; kPadNorm for padding rows.
+// split_half != 0 (fp16x2 input mode): dst holds, per 16-column block, 16 fp16 "hi" values followed
 // by 16 fp16 "lo" values with hi + lo = the fp32 coordinate to ~22 mantissa bits (same bytes per
 // row as fp32); the norm is then taken of hi + lo so that it matches what the MFMA multiplies.
-__global__ __launch_bounds__(kBlock) void prep_mfma_kernel(const float* __restrict__ x, int64_t n, int d,
-                                                           int dp, int64_t rows_pad,
-                                                           const float* __restrict__ mean, float a,
-                                                           float* __restrict__ xs, float* __restrict__ xt,
-                                                           float* __restrict__ nrm, int split_half)
+// Grid: job0's blocks first (blocks0 of them), then job1's; sample mean from mean_partial.
+__global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
+                                                           const double* __restrict__ mean_partial, int64_t n_mean,
+                                                           float a, int split_half)
 {
-    int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (row >= rows_pad) return;
-    const bool live = row < n;
-    double acc = 0.0;
-    float* xt_row = xt ? xt + (row / kTile) * (int64_t)dp * kTile + (row % kTile) : nullptr;
-    _Float16* xh = reinterpret_cast<_Float16*>(xs) + row * 2 * dp;
-    for (int c = 0; c < dp; ++c) {
+    __shared__ double red[kBlock];
+    __shared__ float smean[SDKDE_MAX_D];
+    __shared__ float raw[kPrepRows][SDKDE_MAX_D + 1];     // a (x - mean)
+    __shared__ float used[kPrepRows][SDKDE_MAX_D + 1];    // the value the first contraction multiplies (hi + lo, or raw)
+    block_mean(mean_partial, d, n_mean, red, smean);
+
+    const bool second = (int)blockIdx.x >= blocks0;
+    const PrepJob& job = second ? job1 : job0;
+    const int64_t r0 = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kPrepRows;
+    _Float16* dst_h = reinterpret_cast<_Float16*>(job.dst);
+
+    for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
+        const int rr = idx / dp, c = idx % dp;
+        const int64_t row = r0 + rr;
         float v = 0.0f;
-        if (live && c < d) v = a * (x[row * d + c] - mean[c]);
-        if (xt_row) xt_row[(int64_t)c * kTile] = v;
+        if (row < job.rows && c < d) v = a * (job.src[row * d + c] - smean[c]);
+        raw[rr][c] = v;
         if (split_half) {
             const _Float16 hi = (_Float16)v;
             const _Float16 lo = (_Float16)(v - (float)hi);
-            xh[(c / 16) * 32 + (c % 16)] = hi;
-            xh[(c / 16) * 32 + 16 + (c % 16)] = lo;
+            _Float16* out = dst_h + row * 2 * dp + (c / 16) * 32 + (c % 16);
+            out[0] = hi;
+            out[16] = lo;
             v = (float)hi + (float)lo;
         } else {
-            xs[row * dp + c] = v;
+            job.dst[row * dp + c] = v;
         }
-        acc += (double)v * (double)v;
+        used[rr][c] = v;
     }
-    nrm[row] = live ? -(float)acc : kPadNorm;
+    __syncthreads();
+    if (job.dst_t) {
+        float* base = job.dst_t + (r0 / kTile) * (int64_t)dp * kTile;
+        for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
+            const int tile = idx / (dp * kTile), c = (idx / kTile) % dp, rr = idx % kTile;
+            base[idx] = raw[tile * kTile + rr][c];        // idx = (tile*dp + c)*16 + rr
+        }
+    }
+    if (threadIdx.x < kPrepRows) {
+        double acc = 0.0;
+        for (int c = 0; c < dp; ++c) acc += (double)used[threadIdx.x][c] * (double)used[threadIdx.x][c];
+        const int64_t row = r0 + threadIdx.x;
+        job.dst_n[row] = row < job.rows ? -(float)acc : kPadNorm;
+    }
 }
 
-// Thin-d variant: xs[row][d] = a (x - mean), padding rows get pad_value in every coordinate.
-__global__ __launch_bounds__(kBlock) void prep_thin_kernel(const float* __restrict__ x, int64_t n, int d,
-                                                           int64_t rows_pad, const float* __restrict__ mean,
-                                                           float a, float pad_value, float* __restrict__ xs)
+// Thin-d variant: dst[row][d] = a (x - mean), padding rows get pad_value in every coordinate.
+// One thread per padded row; same two-job grid.
+__global__ __launch_bounds__(kBlock) void prep_thin_kernel(PrepJob job0, PrepJob job1, int blocks0, int d,
+                                                           const double* __restrict__ mean_partial, int64_t n_mean,
+                                                           float a)
 {
-    int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (row >= rows_pad) return;
+    __shared__ double red[kBlock];
+    __shared__ float smean[SDKDE_MAX_D];
+    block_mean(mean_partial, d, n_mean, red, smean);
+    const bool second = (int)blockIdx.x >= blocks0;
+    const PrepJob& job = second ? job1 : job0;
+    const int64_t row = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kBlock + threadIdx.x;
+    if (row >= job.rows_pad) return;
     for (int c = 0; c < d; ++c)
-        xs[row * d + c] = row < n ? a * (x[row * d + c] - mean[c]) : pad_value;
+        job.dst[row * d + c] = row < job.rows ? a * (job.src[row * d + c] - smean[c]) : job.pad_value;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -698,7 +748,6 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
 
 struct Workspace {
     double* mean_partial;
-    float* mean;
     float* xs;  float* xt;  float* xn;     // samples: scaled rows, blocked transpose, -|x|^2
     float* ps;  float* pn;                 // evaluation points (alias xs/xn when they are the samples)
     float* part_t;  float* part_d;
@@ -717,7 +766,6 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base)
         return base ? (char*)base + at : (char*)nullptr;
     };
     w.mean_partial = (double*)take(sizeof(double) * kMeanBlocks * SDKDE_MAX_D);
-    w.mean = (float*)take(sizeof(float) * (SDKDE_MAX_D + 16));
     w.xs = (float*)take(sizeof(float) * p.n_pad * p.dp);
     w.xt = (score && !p.thin) ? (float*)take(sizeof(float) * p.n_pad * p.dp) : nullptr;
     w.xn = (float*)take(sizeof(float) * p.n_pad);
@@ -832,25 +880,30 @@ int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, hipStrea
     return launch_pair<KIND, SDKDE_PREC_FP32>(p, w, st);
 }
 
-// Column means of src[rows][d] into w.mean.
+// First stage of the column means of src[rows][d] (the prep kernels finish them).
 int launch_mean(const float* src, int64_t rows, int d, const Workspace& w, hipStream_t st)
 {
     hipLaunchKernelGGL(mean_partial_kernel, dim3(kMeanBlocks), dim3(kBlock), 0, st, src, rows, d, w.mean_partial);
-    hipLaunchKernelGGL(mean_final_kernel, dim3(1), dim3(SDKDE_MAX_D), 0, st, w.mean_partial, kMeanBlocks, d, rows,
-                       w.mean);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
-// Centre/scale/pad `src` into (dst, dst_t, dst_n) with rows_pad rows.
-int launch_prep(const Plan& p, const float* src, int64_t rows, int64_t rows_pad, float a, const Workspace& w,
-                float* dst, float* dst_t, float* dst_n, float pad_value, uint32_t flags, hipStream_t st)
+// Centre/scale/pad one or two arrays in a single launch (second.src == nullptr: only the first).
+// n_mean: number of rows the column means in w.mean_partial were taken over.
+int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int64_t n_mean, float a,
+                const Workspace& w, uint32_t flags, hipStream_t st)
 {
-    const dim3 grid((unsigned)((rows_pad + kBlock - 1) / kBlock)), block(kBlock);
+    const int64_t per_block = p.thin ? kBlock : kPrepRows;
+    if (first.rows_pad % per_block || (second.src && second.rows_pad % per_block)) return SDKDE_EINVAL;
+    const int64_t blocks0 = first.rows_pad / per_block;
+    const int64_t blocks1 = second.src ? second.rows_pad / per_block : 0;
+    if (blocks0 + blocks1 > 0x7fffffffLL) return SDKDE_EUNSUPPORTED;
+    const dim3 grid((unsigned)(blocks0 + blocks1)), block(kBlock);
     if (p.thin)
-        hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, src, rows, p.d, rows_pad, w.mean, a, pad_value, dst);
+        hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, w.mean_partial,
+                           n_mean, a);
     else
-        hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, src, rows, p.d, p.dp, rows_pad, w.mean, a, dst,
-                           dst_t, dst_n, (flags & 15u) == SDKDE_PREC_FP16X2 ? 1 : 0);
+        hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, p.dp,
+                           w.mean_partial, n_mean, a, (flags & 15u) == SDKDE_PREC_FP16X2 ? 1 : 0);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
@@ -891,9 +944,9 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
 
     const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
     if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
-    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, nullptr, w.xn, kPadCoord, flags, st)) != SDKDE_OK)
-        return rc;
-    if ((rc = launch_prep(p, queries, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, flags, st)) != SDKDE_OK) return rc;
+    const PrepJob sample_job{samples, n, p.n_pad, w.xs, nullptr, w.xn, kPadCoord};
+    const PrepJob query_job{queries, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
+    if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
     rc = laplace ? launch_pair_prec<kEvalLaplace>(p, w, flags, st) : launch_pair_prec<kEval>(p, w, flags, st);
@@ -947,10 +1000,9 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     // When the points are the samples (m == n, so m_pad == n_pad), one prepared array serves
     // as both operands.
     if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
-    if ((rc = launch_prep(p, samples, n, p.n_pad, (float)a, w, w.xs, w.xt, w.xn, kPadCoord, flags, st)) != SDKDE_OK) return rc;
-    if (!self &&
-        (rc = launch_prep(p, points, m, p.m_pad, (float)a, w, w.ps, nullptr, w.pn, 0.0f, flags, st)) != SDKDE_OK)
-        return rc;
+    const PrepJob sample_job{samples, n, p.n_pad, w.xs, w.xt, w.xn, kPadCoord};
+    const PrepJob point_job{self ? nullptr : points, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
+    if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
     rc = self ? launch_pair_prec<kScoreSelf>(p, w, flags, st) : launch_pair_prec<kScorePoints>(p, w, flags, st);
