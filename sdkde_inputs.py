@@ -82,6 +82,33 @@ def mixture_1d(n: int, m: int, seed: int = 0, lo: float = -5.0, hi: float = 6.0)
     return x, q, silverman_bandwidth(x)
 
 
+def mixture_parameters(name: str, seed: int = 0):
+    """(weights[K], means[K,d], variances[K,d]) of the mixture that make(name, seed) draws from
+    (the same first draws of the same generator)."""
+    cfg = CONFIGS[name]
+    if cfg.kind == "mix_1d":
+        return np.array([0.7, 0.3]), np.array([[0.0], [3.0]]), np.array([[1.0], [0.25]])
+    rng = np.random.default_rng(seed)
+    means = 3.0 * rng.standard_normal((cfg.components, cfg.d))
+    if cfg.kind == "mix_diag":
+        variances = rng.uniform(0.5, 2.0, size=(cfg.components, cfg.d))
+    else:
+        variances = np.ones((cfg.components, cfg.d))
+    return np.full(cfg.components, 1.0 / cfg.components), means, variances
+
+
+def true_log_density(q, weights, means, variances) -> np.ndarray:
+    """Log density of the generating mixture at q[m,d] (float64, log-sum-exp over components)."""
+    q = np.asarray(q, dtype=np.float64)
+    logs = []
+    for w, mu, var in zip(weights, means, variances):
+        z = (q - mu) ** 2 / var
+        logs.append(np.log(w) - 0.5 * z.sum(1) - 0.5 * np.log(2 * np.pi * var).sum())
+    logs = np.stack(logs, axis=0)
+    top = logs.max(0)
+    return top + np.log(np.exp(logs - top).sum(0))
+
+
 def make(name: str, seed: int = 0, n: int | None = None, m: int | None = None):
     """Inputs of a named config; n/m may be overridden to get a scaled-down case of the
     same distribution."""
