@@ -15,6 +15,13 @@
  *  - h is passed as double so that the derived constants are formed in double and rounded
  *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation) unless
  *    `flags` selects another input mode.
+ *  - Accuracy domain of the matrix path (d >= 4): squared distances are formed as
+ *    |p|^2 + |x|^2 - 2 p.x on mean-centred coordinates, which loses about (R/h)^2 * 2^-24 in
+ *    the exponent of phi (R = distance of a point from the sample mean).  The stated 1e-3
+ *    tolerances hold while R/h stays below ~100; the thin path (d <= 3) uses direct
+ *    differences and has no such limit.  No running maximum is kept: a point at which every
+ *    phi_j is below the fp32 range (exponent under -126 ln 2) gets the documented
+ *    all-underflow results instead of a shifted sum.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
  *    arguments give bit-identical outputs.
  *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
