@@ -19,9 +19,9 @@
  *    |p|^2 + |x|^2 - 2 p.x on mean-centred coordinates, which loses about (R/h)^2 * 2^-24 in
  *    the exponent of phi (R = distance of a point from the sample mean).  The stated 1e-3
  *    tolerances hold while R/h stays below ~100; the thin path (d <= 3) uses direct
- *    differences and has no such limit.  No running maximum is kept: a point at which every
- *    phi_j is below the fp32 range (exponent under -126 ln 2) gets the documented
- *    all-underflow results instead of a shifted sum.
+ *    differences and has no such limit.  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
+ *    is kept: a point at which every phi_j is below the fp32 range (exponent under -126 ln 2)
+ *    gets the documented all-underflow results instead of a shifted sum.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
  *    arguments give bit-identical outputs.
  *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
@@ -49,10 +49,16 @@ enum {
     SDKDE_MAX_D = 128,
     /* flags: precision mode of the distance cross term (the Gram-matrix tile of the Method section) */
     SDKDE_PREC_FP32 = 0,    /* fp32 MFMA inputs, fp32 accumulate: the reference path */
-    SDKDE_PREC_FP16X2 = 1   /* each input split into two fp16 halves (hi + lo, ~22 mantissa bits) and
+    SDKDE_PREC_FP16X2 = 1,  /* each input split into two fp16 halves (hi + lo, ~22 mantissa bits) and
                                multiplied on the fp16 matrix units with fp32 accumulate; Phi X, exp and all
                                sums stay fp32.  A lower-precision-input mode: its error is reported
                                separately.  Ignored (fp32 VALU) for d <= 3. */
+    /* flags bit 4: two-pass, max-shifted sums for sdkde_eval, sdkde_eval_laplace and sdkde_score at
+       separate points: a first pass finds max_j of the exponent for every point, the second sums
+       phi_j / max phi, and the logarithm (or the signed density) gets the shift back.  Results then stay
+       finite however far a point is from the samples (the log density never becomes -inf, the score at
+       a far point is that of its nearest samples), at about 1.75x the time of the call. */
+    SDKDE_FLAG_MAX_SHIFT = 16
 };
 
 /*

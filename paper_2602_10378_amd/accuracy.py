@@ -1,4 +1,4 @@
-"""Integrated-error comparison of the estimators the paper studies (its "oracle density
+"""Integrated-error comparison of the estimators the paper studies (its known-density
 benchmark": MISE / MIAE of KDE, Laplace-corrected KDE and SD-KDE against a known mixture density),
 run through the GPU library.
 

@@ -16,6 +16,7 @@ from . import build as _build
 SDKDE_OK = 0
 SDKDE_PREC_FP32 = 0
 SDKDE_PREC_FP16X2 = 1
+SDKDE_FLAG_MAX_SHIFT = 16
 SDKDE_MAX_D = 128
 
 _lib = None

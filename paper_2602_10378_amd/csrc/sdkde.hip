@@ -38,8 +38,10 @@ enum PairKind {
     kScoreSelf = 0,     // D and T at the samples themselves (own sample tiles skipped)
     kScorePoints = 1,   // D and T at separate points
     kEval = 2,          // D only (Gaussian KDE)
-    kEvalLaplace = 3    // sum of phi * (1 + d/2 - r^2/2h^2) (Laplace-corrected KDE; signed)
+    kEvalLaplace = 3,   // sum of phi * (1 + d/2 - r^2/2h^2) (Laplace-corrected KDE; signed)
+    kRowMax = 4         // max_j of the exponent (first pass of the max-shifted mode); kept in the D slot
 };
+constexpr float kNegHuge = -3.0e38f;
 constexpr float kLn2 = 0.693147180559945309f;
 
 inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
@@ -261,7 +263,7 @@ struct RowTiles {
 
 // Writes one wave's partial sums: T^T accumulator (lane (r, g), register v) = coordinate
 // 16mb + 4g + v of row r; D needs the sum over the four lane groups g.
-template <int KB, int NI, bool SCORE>
+template <int KB, int NI, bool SCORE, bool ROWMAX = false>
 __device__ __forceinline__ void store_partials(float* __restrict__ part_t, float* __restrict__ part_d, int64_t slot,
                                                int64_t m_pad, int64_t row0, int r, int g,
                                                const f32x4 (&tsum)[NI][SCORE ? KB : 1], const float (&dsum)[NI])
@@ -276,8 +278,13 @@ __device__ __forceinline__ void store_partials(float* __restrict__ part_t, float
             for (int mb = 0; mb < KB; ++mb) *reinterpret_cast<f32x4*>(dst + mb * 16) = tsum[t][mb];
         }
         float dtot = dsum[t];
-        dtot += __shfl_xor(dtot, 16);
-        dtot += __shfl_xor(dtot, 32);
+        if (ROWMAX) {
+            dtot = fmaxf(dtot, __shfl_xor(dtot, 16));
+            dtot = fmaxf(dtot, __shfl_xor(dtot, 32));
+        } else {
+            dtot += __shfl_xor(dtot, 16);
+            dtot += __shfl_xor(dtot, 32);
+        }
         if (g == 0) part_d[slot * m_pad + row] = dtot;
     }
 }
@@ -286,12 +293,14 @@ template <int KB, int NI, int KIND, int PREC>
 __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const float* __restrict__ ps, const float* __restrict__ pn, const float* __restrict__ xs,
     const float* __restrict__ xt, const float* __restrict__ xn, float* __restrict__ part_t,
-    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0)
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0,
+    const float* __restrict__ shift)
 {
     static_assert(NI >= 2 && NI % 2 == 0, "the software pipeline alternates two accumulator sets");
     constexpr bool SCORE = KIND == kScoreSelf || KIND == kScorePoints;
     constexpr bool SELF = KIND == kScoreSelf;
     constexpr bool LAPLACE = KIND == kEvalLaplace;
+    constexpr bool ROWMAX = KIND == kRowMax;
     constexpr int DP = KB * 16;
     constexpr int NM = 4 * KB;                 // MFMAs per contraction and tile
     constexpr int KT = SCORE ? KB : 1;
@@ -311,11 +320,13 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     // at its own magnitude (keeps the rounding of T and D well below the cancellation in T/D - x).
     f32x4 tacc[NI][KT], tsum[NI][KT];
     float dacc[NI], dsum[NI];
+    float lc0[LAPLACE ? NI : 1];          // Laplace factor constant per row tile: 1 + d/2 + shift_i ln 2
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
-        dacc[t] = dsum[t] = 0.0f;
+        dacc[t] = dsum[t] = ROWMAX ? kNegHuge : 0.0f;
 #pragma unroll
         for (int mb = 0; mb < KT; ++mb) tacc[t][mb] = tsum[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (LAPLACE) lc0[t] = fmaf(shift ? shift[row0 + t * kTile + r] : 0.0f, kLn2, laplace_c0);
     }
 
     // ntiles, tiles_per_split and NI are even (host side), so every span of sample tiles below
@@ -406,21 +417,25 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                 __builtin_amdgcn_sched_barrier(0);
                 if (t == NI - 2) load_a1(jt + 2, cur);    // cur.a1 was last read by the MFMAs above
 
-                phi.x = __builtin_amdgcn_exp2f(c.x);
-                phi.y = __builtin_amdgcn_exp2f(c.y);
-                phi.z = __builtin_amdgcn_exp2f(c.z);
-                phi.w = __builtin_amdgcn_exp2f(c.w);
-                if (LAPLACE) {
-                    // c is the base-2 exponent -r^2/(2h^2) log2(e), so the Laplace factor
-                    // 1 + d/2 - r^2/(2h^2) is laplace_c0 + c ln 2 (Laplace-corrected KDE section).
-                    float acc = dacc[t];
-                    acc = fmaf(phi.x, fmaf(c.x, kLn2, laplace_c0), acc);
-                    acc = fmaf(phi.y, fmaf(c.y, kLn2, laplace_c0), acc);
-                    acc = fmaf(phi.z, fmaf(c.z, kLn2, laplace_c0), acc);
-                    acc = fmaf(phi.w, fmaf(c.w, kLn2, laplace_c0), acc);
-                    dacc[t] = acc;
+                if (ROWMAX) {
+                    dacc[t] = fmaxf(dacc[t], fmaxf(fmaxf(c.x, c.y), fmaxf(c.z, c.w)));
                 } else {
-                    dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
+                    phi.x = __builtin_amdgcn_exp2f(c.x);
+                    phi.y = __builtin_amdgcn_exp2f(c.y);
+                    phi.z = __builtin_amdgcn_exp2f(c.z);
+                    phi.w = __builtin_amdgcn_exp2f(c.w);
+                    if (LAPLACE) {
+                        // c is the base-2 exponent -r^2/(2h^2) log2(e) (less the row's shift), so the Laplace
+                        // factor 1 + d/2 - r^2/(2h^2) is lc0 + c ln 2 (Laplace-corrected KDE section).
+                        float acc = dacc[t];
+                        acc = fmaf(phi.x, fmaf(c.x, kLn2, lc0[t]), acc);
+                        acc = fmaf(phi.y, fmaf(c.y, kLn2, lc0[t]), acc);
+                        acc = fmaf(phi.z, fmaf(c.z, kLn2, lc0[t]), acc);
+                        acc = fmaf(phi.w, fmaf(c.w, kLn2, lc0[t]), acc);
+                        dacc[t] = acc;
+                    } else {
+                        dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
+                    }
                 }
                 c = (wrap2 ? nxt.nj : cur.nj) + nin;             // accumulator init of pair u+2
                 __builtin_amdgcn_sched_barrier(0);
@@ -442,8 +457,10 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
             if (((jt + 1 - s_begin) & (kFlushTiles - 1)) == kFlushTiles - 1) {    // wave-uniform
 #pragma unroll
                 for (int t = 0; t < NI; ++t) {
-                    dsum[t] += dacc[t];
-                    dacc[t] = 0.0f;
+                    if (!ROWMAX) {
+                        dsum[t] += dacc[t];
+                        dacc[t] = 0.0f;
+                    }
 #pragma unroll
                     for (int mb = 0; mb < KT; ++mb) {
                         tsum[t][mb] += tacc[t][mb];
@@ -456,11 +473,11 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     }
 #pragma unroll
     for (int t = 0; t < NI; ++t) {
-        dsum[t] += dacc[t];
+        dsum[t] = ROWMAX ? fmaxf(dsum[t], dacc[t]) : dsum[t] + dacc[t];
 #pragma unroll
         for (int mb = 0; mb < KT; ++mb) tsum[t][mb] += tacc[t][mb];
     }
-    store_partials<KB, NI, SCORE>(part_t, part_d, split, m_pad, row0, r, g, tsum, dsum);
+    store_partials<KB, NI, SCORE, ROWMAX>(part_t, part_d, split, m_pad, row0, r, g, tsum, dsum);
 }
 
 // Diagonal blocks of the score at the samples themselves: every wave pairs its NI row tiles with
@@ -537,20 +554,25 @@ __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
 template <int D, int R, int KIND>
 __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
     const float* __restrict__ ps, const float* __restrict__ xs, float* __restrict__ part_t,
-    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0)
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0,
+    const float* __restrict__ shift)
 {
     constexpr bool SCORE = KIND == kScoreSelf || KIND == kScorePoints;
     constexpr bool LAPLACE = KIND == kEvalLaplace;
+    constexpr bool ROWMAX = KIND == kRowMax;
     const int split = blockIdx.x % nsplit;
     const int64_t row_block = blockIdx.x / nsplit;
     const int64_t row0 = row_block * (kBlock * R) + threadIdx.x;
 
-    float p[R][D], dacc[R], nacc[R][SCORE ? D : 1];
+    // sh[q]: the row's shift (max_j of -r^2, <= 0) in the max-shifted mode, else 0; the squared distance is
+    // accumulated on top of it so that exp2(-(r^2 + sh)) = phi / 2^sh costs no extra instruction.
+    float p[R][D], dacc[R], nacc[R][SCORE ? D : 1], sh[R];
 #pragma unroll
     for (int q = 0; q < R; ++q) {
 #pragma unroll
         for (int k = 0; k < D; ++k) p[q][k] = ps[(row0 + (int64_t)q * kBlock) * D + k];
-        dacc[q] = 0.0f;
+        sh[q] = (!ROWMAX && shift) ? shift[row0 + (int64_t)q * kBlock] : 0.0f;
+        dacc[q] = ROWMAX ? kNegHuge : 0.0f;
 #pragma unroll
         for (int k = 0; k < (SCORE ? D : 1); ++k) nacc[q][k] = 0.0f;
     }
@@ -567,14 +589,19 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
 #pragma unroll
             for (int q = 0; q < R; ++q) {
                 float diff[D];
-                float r2 = 0.0f;
+                float r2 = sh[q];
 #pragma unroll
                 for (int k = 0; k < D; ++k) {
                     diff[k] = xv[k] - p[q][k];
                     r2 = fmaf(diff[k], diff[k], r2);
                 }
+                if (ROWMAX) {
+                    dacc[q] = fmaxf(dacc[q], -r2);
+                    continue;
+                }
                 float phi = __builtin_amdgcn_exp2f(-r2);
-                if (LAPLACE) dacc[q] = fmaf(phi, fmaf(-r2, kLn2, laplace_c0), dacc[q]);   // factor 1 + d/2 - r^2/2h^2
+                // Laplace factor 1 + d/2 - r^2/2h^2, with the true r^2 = r2 - sh
+                if (LAPLACE) dacc[q] = fmaf(phi, fmaf(sh[q] - r2, kLn2, laplace_c0), dacc[q]);
                 else dacc[q] += phi;
                 if (SCORE) {
 #pragma unroll
@@ -639,8 +666,10 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
 
 // log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
 // signed != 0 (Laplace-corrected sum, which may be negative): density = sum * exp(lognorm) only.
+// shift (may be null): per-query base-2 exponent shift of the max-shifted mode.
 __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __restrict__ part_d, int nsplit,
                                                                int64_t m, int64_t m_pad, double lognorm, int is_signed,
+                                                               const float* __restrict__ shift,
                                                                float* __restrict__ density,
                                                                float* __restrict__ log_density)
 {
@@ -648,11 +677,13 @@ __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __re
     if (i >= m) return;
     float dsum = 0.0f;
     for (int s = 0; s < nsplit; ++s) dsum += part_d[(int64_t)s * m_pad + i];
+    // max-shifted mode: the sums were taken of phi / 2^shift
+    const double shift_ln = shift ? (double)shift[i] * 0.69314718055994530942 : 0.0;
     if (is_signed) {
-        if (density) density[i] = (float)((double)dsum * exp(lognorm));
+        if (density) density[i] = (float)((double)dsum * exp(lognorm + shift_ln));
         return;
     }
-    double lp = log((double)dsum) + lognorm;      // -inf when dsum == 0
+    double lp = log((double)dsum) + lognorm + shift_ln;      // -inf when dsum == 0
     if (log_density) log_density[i] = (float)lp;
     if (density) density[i] = (float)exp(lp);
 }
@@ -750,6 +781,7 @@ struct Workspace {
     double* mean_partial;
     float* xs;  float* xt;  float* xn;     // samples: scaled rows, blocked transpose, -|x|^2
     float* ps;  float* pn;                 // evaluation points (alias xs/xn when they are the samples)
+    float* shift;                          // per-point exponent shift of the max-shifted mode (separate points only)
     float* part_t;  float* part_d;
     size_t bytes;
 };
@@ -772,6 +804,7 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base)
     if (separate_points) {
         w.ps = (float*)take(sizeof(float) * p.m_pad * p.dp);
         w.pn = (float*)take(sizeof(float) * p.m_pad);
+        w.shift = (float*)take(sizeof(float) * p.m_pad);
     } else {
         w.ps = w.xs;
         w.pn = w.xn;
@@ -800,7 +833,7 @@ struct Profile {
     } while (0)
 
 template <int KIND, int PREC>
-int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
+int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream_t st)
 {
     const dim3 grid((unsigned)(p.row_blocks * p.nsplit)), block(kBlock);
     if ((int64_t)p.row_blocks * p.nsplit > 0x7fffffffLL) return SDKDE_EUNSUPPORTED;
@@ -811,14 +844,15 @@ int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
 #define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                               \
     do {                                                                                                          \
         hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, KIND, PREC>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt,  \
-                           w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0); \
+                           w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0,  \
+                           shift);                                                                                \
         if constexpr (KIND == kScoreSelf)                                                                         \
             hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_, PREC>), dim3((unsigned)p.row_blocks), block, 0, st,   \
                                w.xs, w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                \
     } while (0)
 #define SDKDE_LAUNCH_THIN(D_, R_)                                                                  \
     hipLaunchKernelGGL((pair_thin_kernel<D_, R_, KIND>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
-                       w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0)
+                       w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0, shift)
 #define SDKDE_CASE_NI(KB_, NI_) \
     case NI_: SDKDE_LAUNCH_MFMA(KB_, NI_); break;
 
@@ -873,11 +907,34 @@ int launch_pair(const Plan& p, const Workspace& w, hipStream_t st)
 }
 
 template <int KIND>
-int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, hipStream_t st)
+int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, const float* shift, hipStream_t st)
 {
     // the thin-d path has no matrix inputs: it runs the same fp32 VALU code for every mode
-    if ((flags & 15u) == SDKDE_PREC_FP16X2 && !p.thin) return launch_pair<KIND, SDKDE_PREC_FP16X2>(p, w, st);
-    return launch_pair<KIND, SDKDE_PREC_FP32>(p, w, st);
+    if ((flags & 15u) == SDKDE_PREC_FP16X2 && !p.thin) return launch_pair<KIND, SDKDE_PREC_FP16X2>(p, w, shift, st);
+    return launch_pair<KIND, SDKDE_PREC_FP32>(p, w, shift, st);
+}
+
+// shift[i] = max over splits of the row maxima left in part_d by a kRowMax pass; on the MFMA path the
+// shift is also folded into the row constant pn (-|p~|^2 - shift), so the main pass needs no extra work.
+__global__ __launch_bounds__(kBlock) void shift_kernel(const float* __restrict__ part_d, int nsplit, int64_t m_pad,
+                                                       float* __restrict__ shift, float* __restrict__ pn)
+{
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= m_pad) return;
+    float mx = kNegHuge;
+    for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, part_d[(int64_t)s * m_pad + i]);
+    shift[i] = mx;
+    if (pn) pn[i] -= mx;
+}
+
+// First pass of the max-shifted mode for separate points: row maxima of the exponent, then shift_kernel.
+int launch_max_shift(const Plan& p, const Workspace& w, uint32_t flags, hipStream_t st)
+{
+    int rc = launch_pair_prec<kRowMax>(p, w, flags, nullptr, st);
+    if (rc != SDKDE_OK) return rc;
+    hipLaunchKernelGGL(shift_kernel, dim3((unsigned)((p.m_pad + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
+                       p.nsplit, p.m_pad, w.shift, p.thin ? nullptr : w.pn);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
 // First stage of the column means of src[rows][d] (the prep kernels finish them).
@@ -910,7 +967,8 @@ int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int6
 int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h, uint32_t flags)
 {
     if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
-    if (d > SDKDE_MAX_D || (flags != SDKDE_PREC_FP32 && flags != SDKDE_PREC_FP16X2)) return SDKDE_EUNSUPPORTED;
+    if (d > SDKDE_MAX_D || (flags & ~(15u | SDKDE_FLAG_MAX_SHIFT)) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2)
+        return SDKDE_EUNSUPPORTED;
     if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
     return SDKDE_OK;
 }
@@ -949,13 +1007,16 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
-    rc = laplace ? launch_pair_prec<kEvalLaplace>(p, w, flags, st) : launch_pair_prec<kEval>(p, w, flags, st);
+    const bool shifted = (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
+    if (shifted && (rc = launch_max_shift(p, w, flags, st)) != SDKDE_OK) return rc;
+    const float* shift = shifted ? w.shift : nullptr;
+    rc = laplace ? launch_pair_prec<kEvalLaplace>(p, w, flags, shift, st) : launch_pair_prec<kEval>(p, w, flags, shift, st);
     if (rc != SDKDE_OK) return rc;
     if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
 
     const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
     hipLaunchKernelGGL(eval_epilogue_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
-                       p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0, density_out, log_density_out);
+                       p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0, shift, density_out, log_density_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
@@ -1005,7 +1066,12 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
-    rc = self ? launch_pair_prec<kScoreSelf>(p, w, flags, st) : launch_pair_prec<kScorePoints>(p, w, flags, st);
+    // at the samples themselves the largest weight is the self pair (exponent 0): nothing to shift
+    const bool shifted = !self && (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
+    if (shifted && (rc = launch_max_shift(p, w, flags, st)) != SDKDE_OK) return rc;
+    const float* shift = shifted ? w.shift : nullptr;
+    rc = self ? launch_pair_prec<kScoreSelf>(p, w, flags, nullptr, st)
+              : launch_pair_prec<kScorePoints>(p, w, flags, shift, st);
     if (rc != SDKDE_OK) return rc;
     if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
 

@@ -51,9 +51,11 @@ def test_workspace_bytes_scales_and_validates():
     with pytest.raises(P.SdkdeError) as e:
         P.sdkde_workspace_bytes(10, 1, 129)
     assert e.value.status == 2
-    with pytest.raises(P.SdkdeError) as e:
-        P.sdkde_workspace_bytes(10, 1, 16, flags=7)
-    assert e.value.status == 2
+    for bad_flags in (7, 32, 16 | 2):
+        with pytest.raises(P.SdkdeError) as e:
+            P.sdkde_workspace_bytes(10, 1, 16, flags=bad_flags)
+        assert e.value.status == 2
+    assert P.sdkde_workspace_bytes(10, 1, 16, flags=P.SDKDE_FLAG_MAX_SHIFT | P.SDKDE_PREC_FP16X2) > 0
 
 
 def test_null_and_invalid_arguments_are_rejected_without_a_device():

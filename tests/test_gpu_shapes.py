@@ -78,3 +78,51 @@ def test_debias_in_place_and_aliasing():
     sa = s.clone()
     P.sdkde_debias(x, sa, 1.3, out=sa)
     assert torch.equal(xa, want) and torch.equal(sa, want)
+
+
+@pytest.mark.parametrize("d", [1, 3, 16, 128])
+def test_max_shift_mode_handles_points_whose_weights_all_underflow(d):
+    # Without the flag these points get density 0 / log density -inf / score 0 (documented); with it the
+    # sums are taken relative to the largest weight and match the oracle's max-shifted evaluation.
+    import torch
+    import paper_2602_10378_amd as P
+    from parity import assert_laplace_close
+    rng = np.random.default_rng(50 + d)
+    n, m = 3000, 200
+    x = rng.standard_normal((n, d)).astype(np.float32)
+    h = float(sdkde_inputs.silverman_bandwidth(x))
+    q = rng.standard_normal((m, d)).astype(np.float32)
+    if d < 128:
+        # push the queries out until c |q - x|^2 is a few hundred for every sample (i.i.d. data at d = 128
+        # is there already with a rule-of-thumb bandwidth)
+        direction = q / np.linalg.norm(q, axis=1, keepdims=True)
+        q = (q + direction * (25.0 * h + 4.0)).astype(np.float32)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    _, plain = P.sdkde_eval(xd, qd, h, want="log")
+    assert torch.isinf(plain).any()                   # the regime this test is about
+    flags = P.SDKDE_FLAG_MAX_SHIFT
+    dens, logd = P.sdkde_eval(xd, qd, h, want="both", flags=flags)
+    ref = oracle.eval_log_density(x, q, h)
+    assert_log_density_close(logd.cpu().numpy(), ref, f"shifted eval d={d}")
+    sp = P.sdkde_score(xd, h, points=qd, flags=flags).cpu().numpy()
+    assert_score_close(sp, oracle.score(x, h, points=q), f"shifted score at points d={d}")
+    if d <= 16:
+        lap = P.sdkde_eval_laplace(xd, qd, h, flags=flags).cpu().numpy()
+        lref, labs = oracle.eval_laplace_density(x, q, h), oracle.eval_laplace_abs_density(x, q, h)
+        assert np.all(np.isfinite(lap))
+        ok = labs > 1e-36                               # where the signed density is representable in fp32 at all
+        if ok.any():
+            assert_laplace_close(lap[ok], lref[ok], labs[ok], f"shifted laplace d={d}")
+        # a nearer ring of queries, where plain fp32 sums are tiny but the densities are representable
+        q2 = (x[:m] + 6.0 * h * direction).astype(np.float32)
+        lap2 = P.sdkde_eval_laplace(xd, torch.from_numpy(q2).cuda(), h, flags=flags).cpu().numpy()
+        assert_laplace_close(lap2, oracle.eval_laplace_density(x, q2, h), oracle.eval_laplace_abs_density(x, q2, h),
+                             f"shifted laplace ring d={d}")
+    # the flag changes nothing where no shift is needed (queries among the samples), beyond rounding
+    near = torch.from_numpy(x[:100].copy()).cuda()
+    _, a = P.sdkde_eval(xd, near, h, want="log")
+    _, b = P.sdkde_eval(xd, near, h, want="log", flags=flags)
+    assert float((a - b).abs().max()) < 1e-4
+    # and the fp16x2 input mode composes with it
+    _, c = P.sdkde_eval(xd, qd, h, want="log", flags=flags | P.SDKDE_PREC_FP16X2)
+    assert_log_density_close(c.cpu().numpy(), ref, f"shifted fp16x2 eval d={d}")
