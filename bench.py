@@ -110,24 +110,28 @@ def main():
     logd_fp32 = logd.clone()
     other = None
     if not args.no_other_modes and d > 3:
-        # Lower-precision-input mode, reported separately: same steps, same timing protocol.
-        step(P.SDKDE_PREC_FP16X2)
-        torch.cuda.synchronize()
-        P.sdkde_profile_enable(True)
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            step(P.SDKDE_PREC_FP16X2)
-        torch.cuda.synchronize()
-        dt16 = time.perf_counter() - t1
-        l16, ms16 = P.sdkde_profile_summary(0)
-        P.sdkde_profile_enable(False)
-        other = {"fp16x2_inputs": {
-            "value": (float(n) * n + float(m) * n) / (dt16 / args.steps), "unit": "pairs/s",
-            "ms_per_step": dt16 / args.steps * 1e3, "score_main_kernel_ms": ms16 / max(l16, 1),
-            "score_rel_frobenius_vs_fp32_path": float((s - s_fp32).norm() / s_fp32.norm()),
-            "max_abs_log_density_diff_vs_fp32_path": float((logd - logd_fp32).abs().max()),
-            "note": "cross-term inputs split into fp16 hi+lo on the fp16 matrix units, fp32 accumulate; "
-                    "error vs the oracle is measured in tests/test_gpu_full_size.py"}}
+        # Lower-precision-input modes, reported separately: same steps, same timing protocol.
+        other = {}
+        notes = {"fp16x2_inputs": "cross-term inputs split into fp16 hi+lo on the fp16 matrix units, fp32 accumulate",
+                 "fp16x2_all": "both contractions on the fp16 matrix units (inputs and Phi split into fp16 hi+lo), "
+                               "fp32 accumulate, exp and row sums fp32"}
+        for key, flags in (("fp16x2_inputs", P.SDKDE_PREC_FP16X2), ("fp16x2_all", P.SDKDE_PREC_FP16X2_ALL)):
+            step(flags)
+            torch.cuda.synchronize()
+            P.sdkde_profile_enable(True)
+            t1 = time.perf_counter()
+            for _ in range(args.steps):
+                step(flags)
+            torch.cuda.synchronize()
+            dt16 = time.perf_counter() - t1
+            l16, ms16 = P.sdkde_profile_summary(0)
+            P.sdkde_profile_enable(False)
+            other[key] = {
+                "value": (float(n) * n + float(m) * n) / (dt16 / args.steps), "unit": "pairs/s",
+                "ms_per_step": dt16 / args.steps * 1e3, "score_main_kernel_ms": ms16 / max(l16, 1),
+                "score_rel_frobenius_vs_fp32_path": float((s - s_fp32).norm() / s_fp32.norm()),
+                "max_abs_log_density_diff_vs_fp32_path": float((logd - logd_fp32).abs().max()),
+                "note": notes[key] + "; error vs the oracle is measured in tests/test_gpu_full_size.py"}
         s.copy_(s_fp32)
 
     pairs = float(n) * n + float(m) * n

@@ -53,6 +53,10 @@ enum {
                                multiplied on the fp16 matrix units with fp32 accumulate; Phi X, exp and all
                                sums stay fp32.  A lower-precision-input mode: its error is reported
                                separately.  Ignored (fp32 VALU) for d <= 3. */
+    SDKDE_PREC_FP16X2_ALL = 2, /* as FP16X2, and Phi X on the fp16 matrix units too: Phi is split in registers
+                               into fp16 hi + lo (scaled by 2^14 to stay normal), X into hi + lo in the
+                               prepared copy; fp32 accumulate, exp and the row sums D stay fp32.  For calls
+                               without a Phi X contraction (eval) identical to FP16X2. */
     /* flags bit 4: two-pass, max-shifted sums for sdkde_eval, sdkde_eval_laplace and sdkde_score at
        separate points: a first pass finds max_j of the exponent for every point, the second sums
        phi_j / max phi, and the logarithm (or the signed density) gets the shift back.  Results then stay

@@ -16,6 +16,7 @@ from . import build as _build
 SDKDE_OK = 0
 SDKDE_PREC_FP32 = 0
 SDKDE_PREC_FP16X2 = 1
+SDKDE_PREC_FP16X2_ALL = 2
 SDKDE_FLAG_MAX_SHIFT = 16
 SDKDE_MAX_D = 128
 
@@ -82,14 +83,15 @@ def sdkde_workspace_bytes(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) 
     return int(out.value)
 
 
-def make_workspace(n: int, m: int, d: int, device="cuda") -> torch.Tensor:
-    """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes."""
-    return torch.empty(sdkde_workspace_bytes(n, m, d), dtype=torch.uint8, device=device)
+def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PREC_FP16X2_ALL) -> torch.Tensor:
+    """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes (by default sized for
+    the mode with the largest footprint, so one buffer serves every precision mode)."""
+    return torch.empty(sdkde_workspace_bytes(n, m, d, flags), dtype=torch.uint8, device=device)
 
 
-def _workspace(ws, n, m, d, device):
+def _workspace(ws, n, m, d, device, flags=SDKDE_PREC_FP16X2_ALL):
     if ws is None:
-        ws = make_workspace(n, m, d, device)
+        ws = make_workspace(n, m, d, device, flags & 15)
     if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
         raise TypeError("workspace must be a contiguous uint8 tensor on the GPU")
     return ws

@@ -28,17 +28,37 @@ def is_stale() -> bool:
     return any(os.path.getmtime(p) > built for p in SOURCES + HEADERS)
 
 
+def kernels_using_scratch(remarks: str):
+    """Names of kernels whose resource-usage remarks report a non-zero scratch size."""
+    import re
+    out, name = [], None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
+        if m and int(m.group(1)) > 0 and name:
+            out.append(name)
+    return out
+
+
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile the library; with force=False only when a source is newer than the binary."""
     if not force and not is_stale():
         return LIBRARY
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", LIBRARY, *SOURCES]
+    cmd = [hipcc, *HIPCC_FLAGS, "-Rpass-analysis=kernel-resource-usage", "-I", os.path.join(ROOT, "include"),
+           "-o", LIBRARY, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + proc.stdout)
+        lines = [ln for ln in proc.stdout.splitlines() if "remark:" not in ln]
+        raise RuntimeError("hipcc failed:\n" + "\n".join(lines))
+    spilled = kernels_using_scratch(proc.stdout)
+    if spilled:
+        os.remove(LIBRARY)
+        raise RuntimeError("kernels spill registers to scratch memory (not allowed in this library): " + ", ".join(spilled))
     flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
     proc = subprocess.run([hipcc, *flags, "-o", PEAKS_BINARY, PEAKS_SOURCE], stdout=subprocess.PIPE,
                           stderr=subprocess.STDOUT, text=True)

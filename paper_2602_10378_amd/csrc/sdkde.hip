@@ -109,13 +109,16 @@ constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (tw
 //   dst[row][dp]   = a (x - mean), 0 in padding columns and rows (coalesced row writes),
 //   dst_t[row/16][col][row%16] = the same values with each 16-sample tile transposed (if dst_t),
 //   dst_n[row]     = -|dst[row]|^2 in double, rounded once; kPadNorm for padding rows.
-// split_half != 0 (fp16x2 input mode): dst holds, per 16-column block, 16 fp16 "hi" values followed
-// by 16 fp16 "lo" values with hi + lo = the fp32 coordinate to ~22 mantissa bits (same bytes per
-// row as fp32); the norm is then taken of hi + lo so that it matches what the MFMA multiplies.
+// prec >= SDKDE_PREC_FP16X2 (fp16x2 input modes): dst holds, per 16-column block, 16 fp16 "hi" values
+// followed by 16 fp16 "lo" values with hi + lo = the fp32 coordinate to ~22 mantissa bits (same bytes
+// per row as fp32); the norm is then taken of hi + lo so that it matches what the MFMA multiplies.
+// prec == SDKDE_PREC_FP16X2_ALL: dst_t holds fp16 pairs too, laid out as the A operand of the K = 32
+// second contraction: for tile, column c and lane group g, eight halves [hi(4g..4g+3) | the same again]
+// followed by eight halves [lo(4g..4g+3) | the same again] (twice the bytes of the fp32 layout).
 // Grid: job0's blocks first (blocks0 of them), then job1's; sample mean from mean_partial.
 __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
                                                            const double* __restrict__ mean_partial, int64_t n_mean,
-                                                           float a, int split_half)
+                                                           float a, int prec)
 {
     __shared__ double red[kBlock];
     __shared__ float smean[SDKDE_MAX_D];
@@ -134,7 +137,7 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
         float v = 0.0f;
         if (row < job.rows && c < d) v = a * (job.src[row * d + c] - smean[c]);
         raw[rr][c] = v;
-        if (split_half) {
+        if (prec != SDKDE_PREC_FP32) {
             const _Float16 hi = (_Float16)v;
             const _Float16 lo = (_Float16)(v - (float)hi);
             _Float16* out = dst_h + row * 2 * dp + (c / 16) * 32 + (c % 16);
@@ -147,11 +150,20 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
         used[rr][c] = v;
     }
     __syncthreads();
-    if (job.dst_t) {
+    if (job.dst_t && prec != SDKDE_PREC_FP16X2_ALL) {
         float* base = job.dst_t + (r0 / kTile) * (int64_t)dp * kTile;
         for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
             const int tile = idx / (dp * kTile), c = (idx / kTile) % dp, rr = idx % kTile;
             base[idx] = raw[tile * kTile + rr][c];        // idx = (tile*dp + c)*16 + rr
+        }
+    } else if (job.dst_t) {
+        _Float16* base = reinterpret_cast<_Float16*>(job.dst_t) + (r0 / kTile) * (int64_t)dp * 64;
+        for (int idx = threadIdx.x; idx < kPrepRows * dp * 4; idx += kBlock) {
+            // idx = ((tile*dp + c)*4 + g)*16 + e
+            const int e = idx % 16, g = (idx / 16) % 4, c = (idx / 64) % dp, tile = idx / (64 * dp);
+            const float v = raw[tile * kTile + 4 * g + (e & 3)][c];
+            const _Float16 hi = (_Float16)v;
+            base[idx] = e < 8 ? hi : (_Float16)(v - (float)hi);
         }
     }
     if (threadIdx.x < kPrepRows) {
@@ -210,6 +222,26 @@ __global__ __launch_bounds__(kBlock) void prep_thin_kernel(PrepJob job0, PrepJob
 //   ps, pn : m_pad rows (multiple of kRowPad >= RB);  xs, xt, xn : ntiles*16 rows.
 // ------------------------------------------------------------------------------------------
 
+// fp16x2-all mode: Phi is produced as 2^kPhiScaleLog2 * phi (the offset rides on the row constant, so it
+// is free) so that values down to 2^-28 keep full fp16 precision; phi <= 1 keeps the product below 65504.
+constexpr int kPhiScaleLog2 = 14;
+
+// [hi(x) hi(y) hi(z) hi(w) | lo(x) lo(y) lo(z) lo(w)] with hi = fp16(phi) (toward zero) and
+// lo = fp16(phi - hi).  The residual is formed by the mixed-precision FMA (fp32 phi * 1.0 - fp16 hi, result
+// rounded to fp16 into one half of the destination): six VALU instructions for four values.
+__device__ __forceinline__ f16x8 split_phi(const f32x4& phi)
+{
+    const uint32_t h01 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(phi.x, phi.y));
+    const uint32_t h23 = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(phi.z, phi.w));
+    uint32_t l01, l23;      // mixlo leaves the upper half as it was; mixhi then writes it
+    asm("v_fma_mixlo_f16 %0, %1, 1.0, -%2 op_sel_hi:[0,0,1]" : "=v"(l01) : "v"(phi.x), "v"(h01));
+    asm("v_fma_mixhi_f16 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "+v"(l01) : "v"(phi.y), "v"(h01));
+    asm("v_fma_mixlo_f16 %0, %1, 1.0, -%2 op_sel_hi:[0,0,1]" : "=v"(l23) : "v"(phi.z), "v"(h23));
+    asm("v_fma_mixhi_f16 %0, %1, 1.0, -%2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "+v"(l23) : "v"(phi.w), "v"(h23));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(f16x8, (u32x4){h01, h23, l01, l23});
+}
+
 // Row-tile operands of one wave for NI row tiles starting at row0: -|p~|^2 and the B operand 2 * p~.
 // fp32 inputs: lane (r, g) holds coordinates 16kb + 4g .. +3 of row r (b[t][kb]).
 // fp16x2 inputs: two K = 32 operands per 16-column block, bh[t][kb][0] = [hi | hi] and
@@ -219,7 +251,7 @@ __global__ __launch_bounds__(kBlock) void prep_thin_kernel(PrepJob job0, PrepJob
 template <int KB, int NI, int PREC>
 struct RowTiles {
     f32x4 b[PREC == SDKDE_PREC_FP32 ? NI : 1][KB];
-    f16x8 bh[PREC == SDKDE_PREC_FP16X2 ? NI : 1][KB][2];
+    f16x8 bh[PREC != SDKDE_PREC_FP32 ? NI : 1][KB][2];
     float ni[NI];
 
     __device__ __forceinline__ void load(const float* __restrict__ ps, const float* __restrict__ pn, int64_t row0,
@@ -313,6 +345,11 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 
     RowTiles<KB, NI, PREC> rows;
     rows.load(ps, pn, row0, r, g);
+    if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
+        // every Phi of this kernel carries the factor 2^kPhiScaleLog2 (exact; removed from the sums at the end)
+#pragma unroll
+        for (int t = 0; t < NI; ++t) rows.ni[t] += (float)kPhiScaleLog2;
+    }
     const float (&ni)[NI] = rows.ni;
 
     // Two-level accumulation: the running sums (tacc, dacc) are folded into (tsum, dsum) every
@@ -336,9 +373,13 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const int dt0 = (int)(row0 / kTile);          // the wave's own row tiles are sample tiles dt0 .. dt0+NI-1
 
     // Operands of one sample tile, as each lane holds them.
+    constexpr bool HALF2 = PREC == SDKDE_PREC_FP16X2_ALL;      // second contraction on the fp16 units too
     struct Operands {
-        f32x4 a1[KB];     // first contraction, A: lane (r, g) = coordinates 16kb + 4g .. +3 of sample r
+        f32x4 a1[KB];     // first contraction, A: the lane's 16 bytes of sample r's row, block kb (fp32: coordinates
+                          // 16kb + 4g .. +3; fp16x2: elements 8g .. 8g+7 of [hi | lo])
         f32x4 a2[KT];     // second contraction, A: lane (r, g) = coordinate 16mb + r of samples 4g .. 4g+3
+                          // (fp32), or the eight halves [hi(4g..4g+3) | again] when HALF2
+        f32x4 a2lo[HALF2 ? KT : 1];   // HALF2 only: [lo(4g..4g+3) | again]
         f32x4 nj;         // -|x|^2 of samples 4g .. 4g+3
     };
     Operands set_a, set_b;
@@ -360,11 +401,19 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
             for (int kb = 0; kb < KB; ++kb) o.a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
         };
         auto load_a2 = [&](int jt, Operands& o) {
-            if (SCORE) {
+            if (SCORE && !HALF2) {
                 const float* trow = xt + ((int64_t)min(jt, t_last) * DP + r) * kTile + g * 4;
 #pragma unroll
                 for (int mb = 0; mb < KB; ++mb)
                     o.a2[mb] = *reinterpret_cast<const f32x4*>(trow + mb * 16 * kTile);
+            } else if (SCORE) {
+                // 32 bytes per (column, lane group): [hi | hi] then [lo | lo]
+                const float* trow = xt + (((int64_t)min(jt, t_last) * DP + r) * 4 + g) * 8;
+#pragma unroll
+                for (int mb = 0; mb < KB; ++mb) {
+                    o.a2[mb] = *reinterpret_cast<const f32x4*>(trow + mb * 16 * 32);
+                    o.a2lo[mb] = *reinterpret_cast<const f32x4*>(trow + mb * 16 * 32 + 4);
+                }
             }
         };
         auto load_nj = [&](int jt, Operands& o) {
@@ -438,13 +487,27 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                     }
                 }
                 c = (wrap2 ? nxt.nj : cur.nj) + nin;             // accumulator init of pair u+2
+                f16x8 bphi;
+                if (SCORE && HALF2) bphi = split_phi(phi);       // part of the same VALU clump
                 __builtin_amdgcn_sched_barrier(0);
 
-                if (SCORE) {
+                if (SCORE && !HALF2) {
 #pragma unroll
                     for (int i = 0; i < NM; ++i) {
                         const int v = i / KB, mb = i % KB;     // the KB accumulator chains interleave
                         tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(cur.a2[mb][v], phi[v], tacc[t][mb], 0, 0, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                } else if (SCORE) {
+                    // Phi^T split as hi + lo (fp16 each; Phi carries a factor 2^14 so that its small values
+                    // stay normal in fp16): K = 32 is [hi(4 samples) | lo(4 samples)] per lane group, against
+                    // [x_hi | x_hi] and [x_lo | x_lo]: two MFMAs give (phi_hi + phi_lo)(x_hi + x_lo).
+#pragma unroll
+                    for (int mb = 0; mb < KB; ++mb) {
+                        tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, cur.a2[mb]), bphi,
+                                                                             tacc[t][mb], 0, 0, 0);
+                        tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, cur.a2lo[mb]), bphi,
+                                                                             tacc[t][mb], 0, 0, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -476,6 +539,12 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         dsum[t] = ROWMAX ? fmaxf(dsum[t], dacc[t]) : dsum[t] + dacc[t];
 #pragma unroll
         for (int mb = 0; mb < KT; ++mb) tsum[t][mb] += tacc[t][mb];
+        if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
+            constexpr float unscale = 1.0f / (float)(1 << kPhiScaleLog2);
+            dsum[t] *= unscale;
+#pragma unroll
+            for (int mb = 0; mb < KT; ++mb) tsum[t][mb] *= unscale;
+        }
     }
     store_partials<KB, NI, SCORE, ROWMAX>(part_t, part_d, split, m_pad, row0, r, g, tsum, dsum);
 }
@@ -499,6 +568,10 @@ __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
 
     RowTiles<KB, NI, PREC> rows;
     rows.load(xs, xn, row0, r, g);
+    if (PREC == SDKDE_PREC_FP16X2_ALL) {      // Phi carries 2^kPhiScaleLog2, as in pair_mfma_kernel
+#pragma unroll
+        for (int t = 0; t < NI; ++t) rows.ni[t] += (float)kPhiScaleLog2;
+    }
     f32x4 tsum[NI][KB];
     float dsum[NI];
 #pragma unroll
@@ -511,13 +584,22 @@ __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
     for (int dt = 0; dt < NI; ++dt) {
         const int jt = dt0 + dt;
         if (jt >= ntiles) break;               // rows past the last sample tile are padding
-        f32x4 a1[KB], a2[KB];
+        constexpr bool HALF2 = PREC == SDKDE_PREC_FP16X2_ALL;
+        f32x4 a1[KB], a2[KB], a2lo[HALF2 ? KB : 1];
         const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
-        const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) {
-            a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
-            a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * kTile);
+        for (int kb = 0; kb < KB; ++kb) a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
+        if (!HALF2) {
+            const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * kTile);
+        } else {
+            const float* trow = xt + (((int64_t)jt * DP + r) * 4 + g) * 8;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * 32);
+                a2lo[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * 32 + 4);
+            }
         }
         const f32x4 nj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
 #pragma unroll
@@ -534,11 +616,29 @@ __global__ __launch_bounds__(kBlock) void pair_diag_kernel(
                 phi[v] = (own && g * 4 + v == r) ? 0.0f : e;
             }
             dsum[t] += (phi.x + phi.y) + (phi.z + phi.w);
+            if (!HALF2) {
 #pragma unroll
-            for (int mb = 0; mb < KB; ++mb)
+                for (int mb = 0; mb < KB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tsum[t][mb], 0, 0, 0);
+                    for (int v = 0; v < 4; ++v)
+                        tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tsum[t][mb], 0, 0, 0);
+            } else {
+                const f16x8 bphi = split_phi(phi);
+#pragma unroll
+                for (int mb = 0; mb < KB; ++mb) {
+                    tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2[mb]), bphi, tsum[t][mb], 0, 0, 0);
+                    tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2lo[mb]), bphi, tsum[t][mb], 0, 0, 0);
+                }
+            }
+        }
+    }
+    if (PREC == SDKDE_PREC_FP16X2_ALL) {
+        constexpr float unscale = 1.0f / (float)(1 << kPhiScaleLog2);
+#pragma unroll
+        for (int t = 0; t < NI; ++t) {
+            dsum[t] *= unscale;
+#pragma unroll
+            for (int mb = 0; mb < KB; ++mb) tsum[t][mb] *= unscale;
         }
     }
     store_partials<KB, NI, true>(part_t, part_d, slot, m_pad, row0, r, g, tsum, dsum);
@@ -699,6 +799,24 @@ __global__ __launch_bounds__(kBlock) void debias_kernel(const float* __restrict_
 // Host side: plan, workspace layout, dispatch.
 // ------------------------------------------------------------------------------------------
 
+// Most row tiles per wave for which pair_mfma_kernel is instantiated (larger ones would spill registers).
+constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
+{
+    const bool second = kind == kScoreSelf || kind == kScorePoints;     // has the Phi X contraction
+    if (prec == SDKDE_PREC_FP16X2_ALL && kb > 6) return 0;              // see effective_prec()
+    return second ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+}
+
+// Precision mode a call actually runs in: the thin path is fp32 VALU code; the fp16 second contraction is
+// built for dp <= 96 (beyond that its operands no longer fit the register file) and falls back to fp16x2.
+inline uint32_t effective_prec(uint32_t flags, bool thin, int dp)
+{
+    const uint32_t prec = flags & 15u;
+    if (thin) return SDKDE_PREC_FP32;
+    if (prec == SDKDE_PREC_FP16X2_ALL && dp > 96) return SDKDE_PREC_FP16X2;
+    return prec;
+}
+
 struct Plan {
     bool thin;
     int d, dp;            // true and padded dimension (thin: dp == d)
@@ -740,7 +858,7 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
     } else {
         const int kb = p.dp / 16;
         // measured: more row tiles per wave (operand reuse) beats a second wave per SIMD once dp >= 48
-        const int top = score ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+        const int top = max_row_tiles(kb, score ? kScoreSelf : kEval);
         for (int v = top; v >= 2; v /= 2) cand[nc++] = v;
     }
     const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
@@ -748,7 +866,7 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score)
     {
         // a forced value must be one the dispatch tables below instantiate
         const int kb = p.thin ? 0 : p.dp / 16;
-        const int widest = p.thin ? 4 : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+        const int widest = p.thin ? 4 : max_row_tiles(kb, score ? kScoreSelf : kEval);
         const int narrowest = p.thin ? 1 : 2;
         if (forced_ni >= narrowest && forced_ni <= widest && (forced_ni & (forced_ni - 1)) == 0) {
             cand[0] = forced_ni;
@@ -788,7 +906,7 @@ struct Workspace {
 
 // Lays out the workspace for `plan`; base may be null (size query).  separate_points: the
 // evaluation points are an array of their own (eval, or score at points != samples).
-Workspace layout(const Plan& p, bool score, bool separate_points, void* base)
+Workspace layout(const Plan& p, bool score, bool separate_points, void* base, uint32_t flags = 0)
 {
     Workspace w{};
     size_t off = 0;
@@ -799,7 +917,9 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base)
     };
     w.mean_partial = (double*)take(sizeof(double) * kMeanBlocks * SDKDE_MAX_D);
     w.xs = (float*)take(sizeof(float) * p.n_pad * p.dp);
-    w.xt = (score && !p.thin) ? (float*)take(sizeof(float) * p.n_pad * p.dp) : nullptr;
+    // blocked transpose for the second contraction: fp32, or hi/lo fp16 pairs stored twice (2x the bytes)
+    const size_t xt_scale = effective_prec(flags, p.thin, p.dp) == SDKDE_PREC_FP16X2_ALL ? 2 : 1;
+    w.xt = (score && !p.thin) ? (float*)take(sizeof(float) * xt_scale * p.n_pad * p.dp) : nullptr;
     w.xn = (float*)take(sizeof(float) * p.n_pad);
     if (separate_points) {
         w.ps = (float*)take(sizeof(float) * p.m_pad * p.dp);
@@ -853,8 +973,11 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
 #define SDKDE_LAUNCH_THIN(D_, R_)                                                                  \
     hipLaunchKernelGGL((pair_thin_kernel<D_, R_, KIND>), grid, block, 0, st, w.ps, w.xs, w.part_t, \
                        w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0, shift)
-#define SDKDE_CASE_NI(KB_, NI_) \
-    case NI_: SDKDE_LAUNCH_MFMA(KB_, NI_); break;
+#define SDKDE_CASE_NI(KB_, NI_)                                            \
+    case NI_:                                                              \
+        if constexpr (NI_ <= max_row_tiles(KB_, KIND, PREC)) SDKDE_LAUNCH_MFMA(KB_, NI_); \
+        else return SDKDE_EUNSUPPORTED;                                    \
+        break;
 
     if (p.thin) {
         const int key = p.d * 10 + p.ni;
@@ -910,7 +1033,13 @@ template <int KIND>
 int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, const float* shift, hipStream_t st)
 {
     // the thin-d path has no matrix inputs: it runs the same fp32 VALU code for every mode
-    if ((flags & 15u) == SDKDE_PREC_FP16X2 && !p.thin) return launch_pair<KIND, SDKDE_PREC_FP16X2>(p, w, shift, st);
+    const uint32_t prec = effective_prec(flags, p.thin, p.dp);
+    constexpr bool has_second = KIND == kScoreSelf || KIND == kScorePoints;
+    if constexpr (has_second) {
+        if (prec == SDKDE_PREC_FP16X2_ALL) return launch_pair<KIND, SDKDE_PREC_FP16X2_ALL>(p, w, shift, st);
+    }
+    // kinds without a second contraction: the two fp16 modes are the same kernel
+    if (prec != SDKDE_PREC_FP32) return launch_pair<KIND, SDKDE_PREC_FP16X2>(p, w, shift, st);
     return launch_pair<KIND, SDKDE_PREC_FP32>(p, w, shift, st);
 }
 
@@ -960,14 +1089,14 @@ int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int6
                            n_mean, a);
     else
         hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, p.dp,
-                           w.mean_partial, n_mean, a, (flags & 15u) == SDKDE_PREC_FP16X2 ? 1 : 0);
+                           w.mean_partial, n_mean, a, (int)effective_prec(flags, p.thin, p.dp));
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
 int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h, uint32_t flags)
 {
     if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
-    if (d > SDKDE_MAX_D || (flags & ~(15u | SDKDE_FLAG_MAX_SHIFT)) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2)
+    if (d > SDKDE_MAX_D || (flags & ~(15u | SDKDE_FLAG_MAX_SHIFT)) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_ALL)
         return SDKDE_EUNSUPPORTED;
     if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
     return SDKDE_OK;
@@ -996,7 +1125,7 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
 
     const Plan p = make_plan(n, m, d, false);
-    const Workspace w = layout(p, false, true, workspace);
+    const Workspace w = layout(p, false, true, workspace, flags);
     if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
 
@@ -1030,11 +1159,11 @@ int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_
     int rc = check_common(bytes, n, m, d, 1.0, flags);
     if (rc != SDKDE_OK) return rc;
     // Largest of: score at the samples themselves, score at m separate points, eval at m queries.
-    size_t need = layout(make_plan(n, n, d, true), true, false, nullptr).bytes;
+    size_t need = layout(make_plan(n, n, d, true), true, false, nullptr, flags).bytes;
     if (m > 0) {
-        size_t b = layout(make_plan(n, m, d, true), true, true, nullptr).bytes;
+        size_t b = layout(make_plan(n, m, d, true), true, true, nullptr, flags).bytes;
         need = b > need ? b : need;
-        b = layout(make_plan(n, m, d, false), false, true, nullptr).bytes;
+        b = layout(make_plan(n, m, d, false), false, true, nullptr, flags).bytes;
         need = b > need ? b : need;
     }
     *bytes = need;
@@ -1053,7 +1182,7 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
 
     const Plan p = make_plan(n, m, d, true);
-    const Workspace w = layout(p, true, !self, workspace);
+    const Workspace w = layout(p, true, !self, workspace, flags);
     if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
 
@@ -1079,7 +1208,7 @@ int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m,
     const float inv_ah2 = (float)(1.0 / (a * h * h));
     hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
                        w.part_t, w.part_d, w.ps, p.nsplit + ((self && !p.thin) ? 1 : 0), m, p.m_pad, d, p.dp,
-                       p.thin ? 1 : (self ? 2 : 0), (!p.thin && (flags & 15u) == SDKDE_PREC_FP16X2) ? 1 : 0, inv_ah2,
+                       p.thin ? 1 : (self ? 2 : 0), effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0, inv_ah2,
                        score_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }

@@ -59,12 +59,14 @@ def test_full_size_sampled_parity(name):
     e_den = assert_density_close(dens[idx].cpu().numpy(), logp_ref, f"{name} eval")
     print(f"{name}: eval on {len(qrows)} queries: log err {e_log:.3g}, density rel err {e_den:.3g}", flush=True)
 
-    # fp16x2 input mode on the same sampled rows (reported separately)
-    s16 = P.sdkde_score(xd, h, workspace=ws, flags=P.SDKDE_PREC_FP16X2)
-    worst16, frob16 = assert_score_close(s16[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref, f"{name} score fp16x2")
-    _, logd16 = P.sdkde_eval(xd, qd, h, want="log", workspace=ws, flags=P.SDKDE_PREC_FP16X2)
-    e16 = assert_log_density_close(logd16[idx].cpu().numpy(), logp_ref, f"{name} eval fp16x2")
-    print(f"{name}: fp16x2 mode: score worst {worst16:.3g} of allowance, rel frobenius {frob16:.3g}; eval log err {e16:.3g}", flush=True)
+    # fp16x2 input modes on the same sampled rows (reported separately)
+    for label, flags in (("fp16x2", P.SDKDE_PREC_FP16X2), ("fp16x2-all", P.SDKDE_PREC_FP16X2_ALL)):
+        s16 = P.sdkde_score(xd, h, workspace=ws, flags=flags)
+        worst16, frob16 = assert_score_close(s16[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref, f"{name} score {label}")
+        _, logd16 = P.sdkde_eval(xd, qd, h, want="log", workspace=ws, flags=flags)
+        e16 = assert_log_density_close(logd16[idx].cpu().numpy(), logp_ref, f"{name} eval {label}")
+        print(f"{name}: {label} mode: score worst {worst16:.3g} of allowance, rel frobenius {frob16:.3g}; "
+              f"eval log err {e16:.3g}", flush=True)
 
     # whole pipeline properties that hold at any size
     x_sd_gpu = P.sdkde_debias(xd, s, h)

@@ -116,18 +116,20 @@ def test_laplace_corrected_kde_matches_oracle(lib, n, m, d, seed):
 
 # fp16x2 input mode (inputs of the distance cross term split into two fp16 halves): a
 # lower-precision-input mode, held to the same tolerances and with its error printed separately.
+@pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (1200, 200, 5, 6), (1100, 130, 20, 7),
                                         (2048, 512, 64, 10), (700, 90, 100, 11), (17, 9, 16, 2), (3000, 500, 1, 0)])
-def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed):
+def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed, mode):
     P, torch = lib
-    print(f"fp16x2 n={n} m={m} d={d}", flush=True)
+    flags = {1: P.SDKDE_PREC_FP16X2, 2: P.SDKDE_PREC_FP16X2_ALL}[mode]
+    print(f"fp16x2 mode {mode} n={n} m={m} d={d}", flush=True)
     x, q, h = _mixture(n, m, d, seed)
     xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
-    s = P.sdkde_score(xd, h, flags=P.SDKDE_PREC_FP16X2)
+    s = P.sdkde_score(xd, h, flags=flags)
     x_sd = P.sdkde_debias(xd, s, h)
-    dens, logd = P.sdkde_eval(x_sd, qd, h, want="both", flags=P.SDKDE_PREC_FP16X2)
-    lap = P.sdkde_eval_laplace(xd, qd, h, flags=P.SDKDE_PREC_FP16X2)
-    sp = P.sdkde_score(xd, h, points=qd, flags=P.SDKDE_PREC_FP16X2)
+    dens, logd = P.sdkde_eval(x_sd, qd, h, want="both", flags=flags)
+    lap = P.sdkde_eval_laplace(xd, qd, h, flags=flags)
+    sp = P.sdkde_score(xd, h, points=qd, flags=flags)
     s_ref, _, logp_ref = oracle.sd_kde_log_density(x, q, h)
     worst, frob = assert_score_close(s.cpu().numpy(), s_ref, f"fp16x2 d={d}")
     e_log = assert_log_density_close(logd.cpu().numpy(), logp_ref, f"fp16x2 d={d}")
@@ -135,7 +137,8 @@ def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed):
     assert_laplace_close(lap.cpu().numpy(), oracle.eval_laplace_density(x, q, h), oracle.eval_laplace_abs_density(x, q, h),
                          f"fp16x2 laplace d={d}")
     assert_score_close(sp.cpu().numpy(), oracle.score(x, h, points=q), f"fp16x2 points d={d}")
-    print(f"fp16x2 d={d}: score rel frobenius {frob:.3g} (worst {worst:.3g} of allowance), log-density err {e_log:.3g}", flush=True)
+    print(f"fp16x2 mode {mode} d={d}: score rel frobenius {frob:.3g} (worst {worst:.3g} of allowance), "
+          f"log-density err {e_log:.3g}", flush=True)
 
 
 def test_single_sample_closed_form(lib):
