@@ -110,6 +110,21 @@ int sdkde_eval(const float *samples_sd, int64_t n, const float *queries, int64_t
                size_t workspace_bytes, uint32_t flags, void *stream);
 
 /*
+ * The whole SD-KDE pass in one call (Method section, opening paragraph: form the empirical SD-KDE,
+ * score + shift, and evaluate the resulting density on the queries): sdkde_score at the samples,
+ * the shift fused into its epilogue, then sdkde_eval of the shifted samples, with the shifted samples
+ * centred on the mean already computed for the samples (two launches fewer than the three calls).
+ *   samples [n, d] in      queries [m, d] in
+ *   score_out [n, d] out, may be NULL      samples_sd_out [n, d] out, required
+ *   density_out / log_density_out [m] out, either may be NULL, not both (unless m = 0)
+ * Results equal those of the three separate calls up to the rounding of the centring.
+ */
+int sdkde_fit_eval(const float *samples, int64_t n, const float *queries, int64_t m, int32_t d,
+                   double h, float *score_out, float *samples_sd_out, float *density_out,
+                   float *log_density_out, void *workspace, size_t workspace_bytes, uint32_t flags,
+                   void *stream);
+
+/*
  * Laplace-corrected KDE (Laplace-corrected KDE section: K_h^LC(x) = K_h(x) (1 + d/2 - |x|^2 / 2h^2),
  * p_LC(q) = (1/n) sum_j K_h^LC(q - x_j)), with the affine factor applied inside the same pass that
  * forms exp(-|q - x_j|^2 / 2h^2) (the fused "Flash-Laplace-KDE" of that section).  It takes the

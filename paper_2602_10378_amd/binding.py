@@ -44,12 +44,13 @@ def load() -> ctypes.CDLL:
     lib.sdkde_score.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_debias.argtypes = [c_fp, c_fp, i64, i32, f64, c_fp, c_fp]
     lib.sdkde_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
+    lib.sdkde_fit_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_eval_laplace.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_status_string.argtypes = [ctypes.c_int]
     lib.sdkde_status_string.restype = ctypes.c_char_p
     lib.sdkde_profile_enable.argtypes = [ctypes.c_int]
     lib.sdkde_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
-    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace",
+    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace", "sdkde_fit_eval",
                  "sdkde_profile_enable", "sdkde_profile_summary"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -161,6 +162,36 @@ def sdkde_eval(samples_sd, queries, h, density_out=None, log_density_out=None, w
         None if log_density_out is None else log_density_out.data_ptr(),
         ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
     return density_out, log_density_out
+
+
+def sdkde_fit_eval(samples, queries, h, score_out=None, samples_sd_out=None, density_out=None, log_density_out=None,
+                   want="density", workspace=None, flags=SDKDE_PREC_FP32, stream=None):
+    """Score at the samples, shift and KDE at the queries in one call.
+    Returns (samples_sd, density, log_density); score_out is filled if given."""
+    x, q = _dev_f32(samples, "samples"), _dev_f32(queries, "queries")
+    n, d = x.shape
+    if q.dim() != 2 or q.shape[1] != d:
+        raise ValueError("queries must be [m, d]")
+    m = q.shape[0]
+    if samples_sd_out is None:
+        samples_sd_out = torch.empty_like(x)
+    if density_out is None and log_density_out is None:
+        if want in ("density", "both"):
+            density_out = torch.empty(m, dtype=torch.float32, device=x.device)
+        if want in ("log", "both"):
+            log_density_out = torch.empty(m, dtype=torch.float32, device=x.device)
+    for t, name, shape in ((score_out, "score_out", x.shape), (samples_sd_out, "samples_sd_out", x.shape),
+                           (density_out, "density_out", (m,)), (log_density_out, "log_density_out", (m,))):
+        if t is not None:
+            _dev_f32(t, name)
+            if tuple(t.shape) != tuple(shape):
+                raise ValueError(f"{name} has the wrong shape")
+    ws = _workspace(workspace, n, m, d, x.device, flags)
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check("sdkde_fit_eval", load().sdkde_fit_eval(
+        x.data_ptr(), n, q.data_ptr(), m, d, float(h), ptr(score_out), samples_sd_out.data_ptr(), ptr(density_out),
+        ptr(log_density_out), ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
+    return samples_sd_out, density_out, log_density_out
 
 
 def sdkde_eval_laplace(samples, queries, h, density_out=None, workspace=None, flags=SDKDE_PREC_FP32, stream=None):

@@ -731,10 +731,11 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
 // mode 2 (MFMA path, at the samples):   score = (T' - p~ D') / (D' + 1) * inv_ah2
 //        where T', D' exclude the pair (i, i), whose weight is exactly 1.
 // inv_ah2 = 1 / (a h^2) undoes the coordinate scaling.  D == 0 gives 0.
+// score and x_sd are both optional outputs; x_sd = x + half_h2 * score (x: the original points, same indexing).
 __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
     const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
     int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, int ps_split_half, float inv_ah2,
-    float* __restrict__ score)
+    float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd)
 {
     int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (idx >= m * d) return;
@@ -761,7 +762,8 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
         float ratio = tsum / dsum;
         out = (mode == 1 ? ratio : ratio - pc) * inv_ah2;
     }
-    score[idx] = out;
+    if (score) score[idx] = out;
+    if (x_sd) x_sd[idx] = fmaf(half_h2, out, x[idx]);      // fused debiasing shift (sdkde_fit_eval)
 }
 
 // log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
@@ -1113,10 +1115,57 @@ int profile_mark(int which, int edge, hipStream_t st)
     return SDKDE_OK;
 }
 
+// Shared body of sdkde_score and of the first half of sdkde_fit_eval.  samples_sd_out (optional, only at
+// the samples themselves): also writes samples + (h^2/2) score from the same epilogue.
+int score_impl(const float* samples, int64_t n, const float* points, int64_t m, int32_t d, double h,
+               float* score_out, float* samples_sd_out, void* workspace, size_t workspace_bytes, uint32_t flags,
+               void* stream)
+{
+    int rc = check_common(samples, n, m, d, h, flags);
+    if (rc != SDKDE_OK) return rc;
+    const bool self = points == nullptr || (points == samples && m == n);
+    if (points == nullptr && m != n) return SDKDE_EINVAL;
+    if (m == 0) return SDKDE_OK;
+    if (!score_out && !samples_sd_out) return SDKDE_EINVAL;
+    if (samples_sd_out && !self) return SDKDE_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+
+    const Plan p = make_plan(n, m, d, true);
+    const Workspace w = layout(p, true, !self, workspace, flags);
+    if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+
+    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));   // sqrt(c log2 e)
+    // When the points are the samples (m == n, so m_pad == n_pad), one prepared array serves
+    // as both operands.
+    if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
+    const PrepJob sample_job{samples, n, p.n_pad, w.xs, w.xt, w.xn, kPadCoord};
+    const PrepJob point_job{self ? nullptr : points, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
+    if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+
+    if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
+    // at the samples themselves the largest weight is the self pair (exponent 0): nothing to shift
+    const bool shifted = !self && (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
+    if (shifted && (rc = launch_max_shift(p, w, flags, st)) != SDKDE_OK) return rc;
+    const float* shift = shifted ? w.shift : nullptr;
+    rc = self ? launch_pair_prec<kScoreSelf>(p, w, flags, nullptr, st)
+              : launch_pair_prec<kScorePoints>(p, w, flags, shift, st);
+    if (rc != SDKDE_OK) return rc;
+    if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
+
+    const int64_t total = m * (int64_t)d;
+    const float inv_ah2 = (float)(1.0 / (a * h * h));
+    hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+                       w.part_t, w.part_d, w.ps, p.nsplit + ((self && !p.thin) ? 1 : 0), m, p.m_pad, d, p.dp,
+                       p.thin ? 1 : (self ? 2 : 0), effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0, inv_ah2,
+                       score_out, samples, (float)(0.5 * h * h), samples_sd_out);
+    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+}
+
 // Shared body of sdkde_eval and sdkde_eval_laplace.
 int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
               float* density_out, float* log_density_out, void* workspace, size_t workspace_bytes, uint32_t flags,
-              void* stream, bool laplace)
+              void* stream, bool laplace, bool reuse_mean = false)
 {
     int rc = check_common(samples, n, m, d, h, flags);
     if (rc != SDKDE_OK) return rc;
@@ -1130,7 +1179,8 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     hipStream_t st = (hipStream_t)stream;
 
     const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
-    if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
+    // reuse_mean: w.mean_partial still holds the column sums of an earlier pass over (nearly) the same points
+    if (!reuse_mean && (rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
     const PrepJob sample_job{samples, n, p.n_pad, w.xs, nullptr, w.xn, kPadCoord};
     const PrepJob query_job{queries, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
     if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
@@ -1173,44 +1223,24 @@ int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_
 int sdkde_score(const float* samples, int64_t n, const float* points, int64_t m, int32_t d, double h,
                 float* score_out, void* workspace, size_t workspace_bytes, uint32_t flags, void* stream)
 {
+    if (!score_out && m != 0) return SDKDE_EINVAL;
+    return score_impl(samples, n, points, m, d, h, score_out, nullptr, workspace, workspace_bytes, flags, stream);
+}
+
+int sdkde_fit_eval(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
+                   float* score_out, float* samples_sd_out, float* density_out, float* log_density_out,
+                   void* workspace, size_t workspace_bytes, uint32_t flags, void* stream)
+{
+    if (!samples_sd_out) return SDKDE_EINVAL;
     int rc = check_common(samples, n, m, d, h, flags);
     if (rc != SDKDE_OK) return rc;
-    const bool self = points == nullptr || (points == samples && m == n);
-    if (points == nullptr && m != n) return SDKDE_EINVAL;
-    if (m == 0) return SDKDE_OK;
-    if (!score_out) return SDKDE_EINVAL;
-    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
-
-    const Plan p = make_plan(n, m, d, true);
-    const Workspace w = layout(p, true, !self, workspace, flags);
-    if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
-
-    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));   // sqrt(c log2 e)
-    // When the points are the samples (m == n, so m_pad == n_pad), one prepared array serves
-    // as both operands.
-    if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
-    const PrepJob sample_job{samples, n, p.n_pad, w.xs, w.xt, w.xn, kPadCoord};
-    const PrepJob point_job{self ? nullptr : points, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
-    if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
-
-    if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
-    // at the samples themselves the largest weight is the self pair (exponent 0): nothing to shift
-    const bool shifted = !self && (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
-    if (shifted && (rc = launch_max_shift(p, w, flags, st)) != SDKDE_OK) return rc;
-    const float* shift = shifted ? w.shift : nullptr;
-    rc = self ? launch_pair_prec<kScoreSelf>(p, w, flags, nullptr, st)
-              : launch_pair_prec<kScorePoints>(p, w, flags, shift, st);
-    if (rc != SDKDE_OK) return rc;
-    if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
-
-    const int64_t total = m * (int64_t)d;
-    const float inv_ah2 = (float)(1.0 / (a * h * h));
-    hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
-                       w.part_t, w.part_d, w.ps, p.nsplit + ((self && !p.thin) ? 1 : 0), m, p.m_pad, d, p.dp,
-                       p.thin ? 1 : (self ? 2 : 0), effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0, inv_ah2,
-                       score_out);
-    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+    if (m > 0 && (!queries || (!density_out && !log_density_out))) return SDKDE_EINVAL;
+    rc = score_impl(samples, n, nullptr, n, d, h, score_out, samples_sd_out, workspace, workspace_bytes, flags, stream);
+    if (rc != SDKDE_OK || m == 0) return rc;
+    // The column means of the samples are still in the workspace; the shifted samples are centred on them
+    // too (any centre is exact, it only has to be near the data), which saves the mean pass.
+    return eval_impl(samples_sd_out, n, queries, m, d, h, density_out, log_density_out, workspace, workspace_bytes,
+                     flags, stream, false, true);
 }
 
 int sdkde_debias(const float* samples, const float* score, int64_t n, int32_t d, double h, float* samples_sd_out,

@@ -141,6 +141,28 @@ def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed, mode):
           f"log-density err {e_log:.3g}", flush=True)
 
 
+@pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (3000, 777, 1, 0), (2048, 512, 64, 10),
+                                        (17, 9, 5, 2)])
+def test_fused_call_matches_oracle_and_three_calls(lib, n, m, d, seed):
+    P, torch = lib
+    print(f"fused n={n} m={m} d={d}", flush=True)
+    x, q, h = _mixture(n, m, d, seed)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    s = torch.empty_like(xd)
+    x_sd, dens, logd = P.sdkde_fit_eval(xd, qd, h, score_out=s, want="both")
+    s_ref, x_sd_ref, logp_ref = oracle.sd_kde_log_density(x, q, h)
+    assert_score_close(s.cpu().numpy(), s_ref, f"fused d={d}")
+    assert_shifted_close(x_sd.cpu().numpy(), x_sd_ref, s_ref, h, f"fused d={d}")
+    assert_log_density_close(logd.cpu().numpy(), logp_ref, f"fused d={d}")
+    assert_density_close(dens.cpu().numpy(), logp_ref, f"fused d={d}")
+    # the separate calls give the same score and shifted samples bit for bit (same kernels, same order)
+    s3 = P.sdkde_score(xd, h)
+    assert torch.equal(s3, s) and torch.equal(P.sdkde_debias(xd, s3, h), x_sd)
+    # without the optional score output
+    x_sd2, _, logd2 = P.sdkde_fit_eval(xd, qd, h, want="log")
+    assert torch.equal(x_sd2, x_sd) and torch.equal(logd2, logd)
+
+
 def test_single_sample_closed_form(lib):
     # n = 1: s(p) = -(p - x1)/h^2 exactly as in the paper's score formula.
     P, torch = lib
