@@ -136,6 +136,20 @@ int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, in
                        double h, float *density_out, void *workspace, size_t workspace_bytes,
                        uint32_t flags, void *stream);
 
+/*
+ * Introspection of the host-side plan (grid decomposition and workspace layout) that a call with these
+ * sizes would use; touches no device.  call: 0 = sdkde_score at the samples, 1 = sdkde_score at m
+ * separate points, 2 = sdkde_eval / sdkde_eval_laplace at m queries.  out (host, at least 20 entries):
+ *   [0] thin path (d <= 3)   [1] padded dimension   [2] row tiles per wave (thin: rows per thread)
+ *   [3] rows per workgroup   [4] row blocks         [5] splits of the sample axis
+ *   [6] sample tiles per split   [7] sample tiles (of 16)   [8] padded sample rows   [9] padded point rows
+ *   [10] workspace bytes     [11..17] byte offsets in the workspace of: prepared samples, their
+ *   blocked transpose, their norms, prepared points, their norms, partial T, partial D (-1 = absent)
+ *   [18] partial slots       [19] size factor of the transposed copy (2 in the FP16X2_ALL mode)
+ */
+int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t flags, int64_t *out,
+                        int32_t out_len);
+
 /* Static, human-readable name of a status code. */
 const char *sdkde_status_string(int status);
 

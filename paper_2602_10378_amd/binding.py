@@ -46,11 +46,12 @@ def load() -> ctypes.CDLL:
     lib.sdkde_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_fit_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_eval_laplace.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
+    lib.sdkde_describe_plan.argtypes = [i64, i64, i32, i32, u32, ctypes.POINTER(ctypes.c_int64), i32]
     lib.sdkde_status_string.argtypes = [ctypes.c_int]
     lib.sdkde_status_string.restype = ctypes.c_char_p
     lib.sdkde_profile_enable.argtypes = [ctypes.c_int]
     lib.sdkde_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
-    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace", "sdkde_fit_eval",
+    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace", "sdkde_fit_eval", "sdkde_describe_plan",
                  "sdkde_profile_enable", "sdkde_profile_summary"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -82,6 +83,18 @@ def sdkde_workspace_bytes(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) 
     out = ctypes.c_size_t(0)
     _check("sdkde_workspace_bytes", load().sdkde_workspace_bytes(n, m, d, flags, ctypes.byref(out)))
     return int(out.value)
+
+
+PLAN_FIELDS = ("thin", "dp", "row_tiles", "rows_per_block", "row_blocks", "splits", "tiles_per_split", "tiles",
+               "n_pad", "m_pad", "workspace_bytes", "off_xs", "off_xt", "off_xn", "off_ps", "off_pn", "off_part_t",
+               "off_part_d", "partial_slots", "xt_scale")
+
+
+def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PREC_FP32) -> dict:
+    """Grid decomposition and workspace layout for call 0 (score at samples), 1 (score at points) or 2 (eval)."""
+    out = (ctypes.c_int64 * len(PLAN_FIELDS))()
+    _check("sdkde_describe_plan", load().sdkde_describe_plan(n, m, d, call, flags, out, len(PLAN_FIELDS)))
+    return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
 
 def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PREC_FP16X2_ALL) -> torch.Tensor:

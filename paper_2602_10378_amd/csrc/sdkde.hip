@@ -1269,6 +1269,28 @@ int sdkde_eval_laplace(const float* samples, int64_t n, const float* queries, in
                      true);
 }
 
+int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t flags, int64_t* out, int32_t out_len)
+{
+    if (!out || out_len < 20 || call < 0 || call > 2) return SDKDE_EINVAL;
+    int rc = check_common(out, n, m, d, 1.0, flags);
+    if (rc != SDKDE_OK) return rc;
+    const bool score = call != 2;
+    const bool separate = call != 0;
+    const int64_t rows = call == 0 ? n : m;
+    const Plan p = make_plan(n, rows, d, score);
+    char* const base = reinterpret_cast<char*>(uintptr_t(1) << 20);      // any aligned non-null address: offsets only
+    const Workspace w = layout(p, score, separate, base, flags);
+    auto off = [&](const void* q) { return q ? (int64_t)((const char*)q - base) : (int64_t)-1; };
+    const int64_t slots = p.nsplit + ((score && !separate && !p.thin) ? 1 : 0);
+    const int64_t xt_scale = effective_prec(flags, p.thin, p.dp) == SDKDE_PREC_FP16X2_ALL ? 2 : 1;
+    const int64_t v[20] = {
+        p.thin ? 1 : 0, p.dp, p.ni, p.rows_per_block, p.row_blocks, p.nsplit, p.tiles_per_split, p.ntiles,
+        p.n_pad, p.m_pad, (int64_t)w.bytes, off(w.xs), off(w.xt), off(w.xn), off(w.ps), off(w.pn),
+        off(w.part_t), off(w.part_d), slots, xt_scale};
+    for (int k = 0; k < 20; ++k) out[k] = v[k];
+    return SDKDE_OK;
+}
+
 const char* sdkde_status_string(int status)
 {
     switch (status) {
