@@ -55,8 +55,16 @@ enum {
                                separately.  Ignored (fp32 VALU) for d <= 3. */
     SDKDE_PREC_FP16X2_ALL = 2, /* as FP16X2, and Phi X on the fp16 matrix units too: Phi is split in registers
                                into fp16 hi + lo (scaled by 2^14 to stay normal), X into hi + lo in the
-                               prepared copy; fp32 accumulate, exp and the row sums D stay fp32.  For calls
-                               without a Phi X contraction (eval) identical to FP16X2. */
+                               prepared copy; fp32 accumulate, exp and the row sums D stay fp32.  The split
+                               resolves a weight to max(2^-22 phi, 2^-39) ABSOLUTE, i.e. relative to a
+                               weight of one, so it is used where such a weight is present: the score at
+                               the samples themselves (own term 1) and the score at separate points
+                               together with SDKDE_FLAG_MAX_SHIFT (largest term 1).  The score error is
+                               then at most n 2^-39 max_j |x_j - mean| / h^2 on top of the FP16X2 mode's;
+                               only a data set in which nearly every sample is isolated (all neighbour
+                               weights under ~1e-7) has scores that small.  A score at separate points
+                               without the shift, and calls without a Phi X contraction (eval), run as
+                               FP16X2. */
     /* flags bit 4: two-pass, max-shifted sums for sdkde_eval, sdkde_eval_laplace and sdkde_score at
        separate points: a first pass finds max_j of the exponent for every point, the second sums
        phi_j / max phi, and the logarithm (or the signed density) gets the shift back.  Results then stay

@@ -819,6 +819,17 @@ inline uint32_t effective_prec(uint32_t flags, bool thin, int dp)
     return prec;
 }
 
+// The fp16 split of 2^14 phi resolves weights with ABSOLUTE precision 2^-39 (the fp16 subnormal step over the
+// scale), which is harmless next to a weight of one: the sample's own term at the samples themselves, the
+// largest term after a max shift.  A score at separate points without that shift has no such anchor (a point
+// whose weights are all below ~1e-7 would lose them in T but not in D), so it runs the fp16x2 mode instead.
+inline uint32_t anchored_flags(uint32_t flags, bool self)
+{
+    if ((flags & 15u) == SDKDE_PREC_FP16X2_ALL && !self && !(flags & SDKDE_FLAG_MAX_SHIFT))
+        return (flags & ~15u) | SDKDE_PREC_FP16X2;
+    return flags;
+}
+
 struct Plan {
     bool thin;
     int d, dp;            // true and padded dimension (thin: dp == d)
@@ -1129,6 +1140,7 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     if (!score_out && !samples_sd_out) return SDKDE_EINVAL;
     if (samples_sd_out && !self) return SDKDE_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+    flags = anchored_flags(flags, self);
 
     const Plan p = make_plan(n, m, d, true);
     const Workspace w = layout(p, true, !self, workspace, flags);
@@ -1277,6 +1289,7 @@ int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t 
     const bool score = call != 2;
     const bool separate = call != 0;
     const int64_t rows = call == 0 ? n : m;
+    if (score) flags = anchored_flags(flags, !separate);
     const Plan p = make_plan(n, rows, d, score);
     char* const base = reinterpret_cast<char*>(uintptr_t(1) << 20);      // any aligned non-null address: offsets only
     const Workspace w = layout(p, score, separate, base, flags);

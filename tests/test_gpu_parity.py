@@ -141,6 +141,39 @@ def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed, mode):
           f"log-density err {e_log:.3g}", flush=True)
 
 
+# A bandwidth well under the rule of thumb in 17-D leaves most samples without close neighbours: the
+# weights that make up the score are then tiny (1e-7 and below), which is where a scaled fp16 split of
+# Phi runs out of range.  The library uses that split only next to a weight of one (header, the
+# FP16X2_ALL mode); the score at separate points must hold the plain tolerance in every mode, the score
+# at the samples the tolerance plus the absolute term the header states.
+@pytest.mark.parametrize("flags", [0, 1, 2, 18])
+def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
+    P, torch = lib
+    n, m, d = 5445, 2306, 17
+    print(f"narrow bandwidth n={n} m={m} d={d} flags={flags}", flush=True)
+    x, q, h = sdkde_inputs.gaussian_mixture(n, m, d, components=1, seed=41)
+    h *= 0.7
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    sp = P.sdkde_score(xd, h, points=qd, flags=flags).cpu().numpy()
+    sp_ref = oracle.score(x, h, points=q)
+    if flags & 16:
+        keep = np.ones(m, bool)
+    else:       # without the shift a point whose weights all underflow in fp32 gets the documented zero
+        keep = np.isfinite(P.sdkde_eval(xd, qd, h, want="log", flags=flags)[1].cpu().numpy())
+        assert keep.mean() > 0.5
+    worst_p, _ = assert_score_close(sp[keep], sp_ref[keep], f"points flags={flags}")
+    s = P.sdkde_score(xd, h, flags=flags).cpu().numpy().astype(np.float64)
+    s_ref = oracle.score(x, h)
+    ref = np.linalg.norm(s_ref, axis=1)
+    allow = 1e-3 * np.maximum(ref, 1e-3 * np.sqrt(np.mean(ref**2)))
+    if (flags & 15) == 2:
+        radius = np.linalg.norm(x - x.mean(0), axis=1).max()
+        allow = allow + n * 2.0**-39 * radius / h**2
+    worst_s = float(np.max(np.linalg.norm(s - s_ref, axis=1) / allow))
+    print(f"narrow bandwidth flags={flags}: points {worst_p:.3g}, samples {worst_s:.3g} of allowance", flush=True)
+    assert worst_s <= 1.0
+
+
 @pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (3000, 777, 1, 0), (2048, 512, 64, 10),
                                         (17, 9, 5, 2)])
 def test_fused_call_matches_oracle_and_three_calls(lib, n, m, d, seed):
