@@ -70,7 +70,16 @@ enum {
        phi_j / max phi, and the logarithm (or the signed density) gets the shift back.  Results then stay
        finite however far a point is from the samples (the log density never becomes -inf, the score at
        a far point is that of its nearest samples), at about 1.75x the time of the call. */
-    SDKDE_FLAG_MAX_SHIFT = 16
+    SDKDE_FLAG_MAX_SHIFT = 16,
+    /* flags bit 5: symmetric score.  phi_ij = phi_ji, so for the score at the samples themselves each
+       unordered pair needs one Gram-matrix entry and one exp, used for both T_i and T_j (an algorithmic saving
+       the paper does not take: "Arithmetic intensity in d dimensions" counts all n^2 pairs).  A separate
+       mode, reported separately and against the same n^2 pair count.  Same results within the same tolerances,
+       still without atomics and bit-reproducible, but more workspace (one partial [T | D] per row for each of
+       up to 64 groups of sample blocks: about 4.6 GiB at n = 2^20, d = 16).  Takes effect where it pays: for
+       sdkde_score at the samples themselves and sdkde_fit_eval with 4 <= d <= 32 and SDKDE_PREC_FP32; ignored
+       otherwise (sdkde_describe_plan tells). */
+    SDKDE_FLAG_SYMMETRIC = 32
 };
 
 /*
@@ -154,6 +163,8 @@ int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, in
  *   [10] workspace bytes     [11..17] byte offsets in the workspace of: prepared samples, their
  *   blocked transpose, their norms, prepared points, their norms, partial T, partial D (-1 = absent)
  *   [18] partial slots       [19] size factor of the transposed copy (2 in the FP16X2_ALL mode)
+ * and, when out_len >= 24: [20] symmetric mode in effect   [21] rows per sample block   [22] blocks per group
+ *   [23] groups (work items = groups (groups + 1) / 2)
  */
 int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t flags, int64_t *out,
                         int32_t out_len);

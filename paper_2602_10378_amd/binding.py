@@ -18,6 +18,7 @@ SDKDE_PREC_FP32 = 0
 SDKDE_PREC_FP16X2 = 1
 SDKDE_PREC_FP16X2_ALL = 2
 SDKDE_FLAG_MAX_SHIFT = 16
+SDKDE_FLAG_SYMMETRIC = 32
 SDKDE_MAX_D = 128
 
 _lib = None
@@ -87,7 +88,8 @@ def sdkde_workspace_bytes(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) 
 
 PLAN_FIELDS = ("thin", "dp", "row_tiles", "rows_per_block", "row_blocks", "splits", "tiles_per_split", "tiles",
                "n_pad", "m_pad", "workspace_bytes", "off_xs", "off_xt", "off_xn", "off_ps", "off_pn", "off_part_t",
-               "off_part_d", "partial_slots", "xt_scale")
+               "off_part_d", "partial_slots", "xt_scale", "symmetric", "sym_block_rows", "sym_blocks_per_group",
+               "sym_groups")
 
 
 def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PREC_FP32) -> dict:
@@ -99,13 +101,15 @@ def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PR
 
 def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PREC_FP16X2_ALL) -> torch.Tensor:
     """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes (by default sized for
-    the mode with the largest footprint, so one buffer serves every precision mode)."""
-    return torch.empty(sdkde_workspace_bytes(n, m, d, flags), dtype=torch.uint8, device=device)
+    the precision mode with the largest footprint, so one buffer serves every precision mode; the symmetric
+    score needs its flag here)."""
+    need = max(sdkde_workspace_bytes(n, m, d, SDKDE_PREC_FP16X2_ALL), sdkde_workspace_bytes(n, m, d, flags))
+    return torch.empty(need, dtype=torch.uint8, device=device)
 
 
-def _workspace(ws, n, m, d, device, flags=SDKDE_PREC_FP16X2_ALL):
+def _workspace(ws, n, m, d, device, flags=SDKDE_PREC_FP32):
     if ws is None:
-        ws = make_workspace(n, m, d, device, flags & 15)
+        ws = make_workspace(n, m, d, device, flags)
     if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
         raise TypeError("workspace must be a contiguous uint8 tensor on the GPU")
     return ws
@@ -127,7 +131,7 @@ def sdkde_score(samples, h, points=None, out=None, workspace=None, flags=SDKDE_P
     _dev_f32(out, "out")
     if tuple(out.shape) != (m, d):
         raise ValueError("out must be [m, d]")
-    ws = _workspace(workspace, n, m, d, x.device)
+    ws = _workspace(workspace, n, m, d, x.device, flags)
     _check("sdkde_score", load().sdkde_score(x.data_ptr(), n, p_ptr, m, d, float(h), out.data_ptr(),
                                              ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
     return out
@@ -168,7 +172,7 @@ def sdkde_eval(samples_sd, queries, h, density_out=None, log_density_out=None, w
             _dev_f32(t, name)
             if t.numel() != m:
                 raise ValueError(f"{name} must have m elements")
-    ws = _workspace(workspace, n, m, d, x.device)
+    ws = _workspace(workspace, n, m, d, x.device, flags)
     _check("sdkde_eval", load().sdkde_eval(
         x.data_ptr(), n, q.data_ptr(), m, d, float(h),
         None if density_out is None else density_out.data_ptr(),
@@ -219,7 +223,7 @@ def sdkde_eval_laplace(samples, queries, h, density_out=None, workspace=None, fl
     _dev_f32(density_out, "density_out")
     if density_out.numel() != m:
         raise ValueError("density_out must have m elements")
-    ws = _workspace(workspace, n, m, d, x.device)
+    ws = _workspace(workspace, n, m, d, x.device, flags)
     _check("sdkde_eval_laplace", load().sdkde_eval_laplace(
         x.data_ptr(), n, q.data_ptr(), m, d, float(h), density_out.data_ptr(), ws.data_ptr(), ws.numel(), flags,
         _stream_handle(stream)))

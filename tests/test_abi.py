@@ -51,11 +51,16 @@ def test_workspace_bytes_scales_and_validates():
     with pytest.raises(P.SdkdeError) as e:
         P.sdkde_workspace_bytes(10, 1, 129)
     assert e.value.status == 2
-    for bad_flags in (7, 32, 16 | 3):
+    for bad_flags in (7, 64, 16 | 3, 32 | 3):
         with pytest.raises(P.SdkdeError) as e:
             P.sdkde_workspace_bytes(10, 1, 16, flags=bad_flags)
         assert e.value.status == 2
     assert P.sdkde_workspace_bytes(10, 1, 16, flags=P.SDKDE_FLAG_MAX_SHIFT | P.SDKDE_PREC_FP16X2) > 0
+    # the symmetric score keeps one partial per group of sample blocks: more workspace where it takes effect
+    sym = P.sdkde_workspace_bytes(1048576, 131072, 16, flags=P.SDKDE_FLAG_SYMMETRIC)
+    assert big < sym < 6 << 30
+    assert P.sdkde_workspace_bytes(1048576, 131072, 64, flags=P.SDKDE_FLAG_SYMMETRIC) == \
+        P.sdkde_workspace_bytes(1048576, 131072, 64)
 
 
 def test_null_and_invalid_arguments_are_rejected_without_a_device():

@@ -75,3 +75,33 @@ def test_full_size_sampled_parity(name):
     assert bool(((x_sd_gpu >= lo - 1e-4) & (x_sd_gpu <= hi + 1e-4)).all()), "shifted sample left the data's bounding box"
     _, logd_sd = P.sdkde_eval(x_sd_gpu, qd, h, want="log", workspace=ws)
     assert torch.isfinite(logd_sd).all()
+
+
+# The symmetric score (separate mode) at the sizes it is reported at: same sampled rows, plus the rows at the
+# edges of its sample blocks (2048 rows at d = 16) and groups of blocks; and against the ordinary path on all
+# rows (both are within tolerance of the oracle on the sample, so they must agree to a few roundings).
+@pytest.mark.parametrize("name", ["C2", "C5"])
+def test_full_size_symmetric_score(name):
+    import torch
+    import paper_2602_10378_amd as P
+    print(f"full-size symmetric {name}", flush=True)
+    x, q, h = sdkde_inputs.make(name, seed=0)
+    n, d = x.shape
+    flags = P.SDKDE_FLAG_SYMMETRIC
+    plan = P.sdkde_describe_plan(n, n, d, 0, flags)
+    assert plan["symmetric"] == 1
+    xd = torch.from_numpy(x).cuda()
+    ws = P.make_workspace(n, 1, d, flags=flags)
+    s = P.sdkde_score(xd, h, workspace=ws, flags=flags)
+    rb, group = plan["sym_block_rows"], plan["sym_block_rows"] * plan["sym_blocks_per_group"]
+    edges = {k * rb + e for k in (1, 2, n // rb - 1) for e in (-1, 0)} | {k * group + e for k in (1, 2) for e in (-1, 0)}
+    rows = np.array(sorted(set(_sample_rows(n, 64).tolist()) | {e for e in edges if 0 <= e < n}), dtype=np.int64)
+    s_ref = oracle.score(x, h, points=x[rows])
+    worst, frob = assert_score_close(s[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref, f"{name} symmetric score")
+    print(f"{name}: symmetric score on {len(rows)} rows: worst {worst:.3g} of allowance, rel frobenius {frob:.3g}",
+          flush=True)
+    s_plain = P.sdkde_score(xd, h, workspace=ws)
+    rel = float((s - s_plain).norm() / s_plain.norm())
+    print(f"{name}: symmetric vs ordinary path, all rows: rel frobenius {rel:.3g}", flush=True)
+    assert rel < 1e-5
+    assert torch.equal(s, P.sdkde_score(xd, h, workspace=ws, flags=flags))      # no atomics: reruns are bitwise equal

@@ -174,6 +174,58 @@ def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
     assert worst_s <= 1.0
 
 
+# Symmetric score (separate mode): every unordered pair of samples computed once.  Sizes span several sample
+# blocks and groups of blocks with ragged tails; the environment overrides force few groups (several blocks per
+# work item, triangular items with more than one block) and the largest block size at small n.
+@pytest.mark.parametrize("n,d,seed,env", [
+    (5000, 16, 0, {}), (5000, 16, 1, {"SDKDE_SYM_GROUPS": "3"}), (3000, 12, 2, {}), (7000, 20, 3, {}),
+    (6100, 32, 4, {"SDKDE_SYM_GROUPS": "4"}), (9000, 16, 5, {"SDKDE_SYM_RB": "2048"}), (4000, 5, 6, {"SDKDE_SYM_GROUPS": "1"}),
+    (600, 16, 7, {}), (17, 8, 8, {}), (1, 16, 9, {})])
+def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
+    P, torch = lib
+    for key in ("SDKDE_SYM_GROUPS", "SDKDE_SYM_RB"):
+        monkeypatch.delenv(key, raising=False)
+    for key, value in env.items():
+        monkeypatch.setenv(key, value)
+    flags = P.SDKDE_FLAG_SYMMETRIC
+    plan = P.sdkde_describe_plan(n, n, d, 0, flags)
+    print(f"symmetric n={n} d={d} env={env} block={plan['sym_block_rows']} per_group={plan['sym_blocks_per_group']} "
+          f"groups={plan['sym_groups']}", flush=True)
+    assert plan["symmetric"] == 1
+    x, q, h = _mixture(n, 8, d, seed)
+    if n == 1:
+        h = 0.7
+    xd = torch.from_numpy(x).cuda()
+    s = P.sdkde_score(xd, h, flags=flags)
+    s_ref = oracle.score(x, h)
+    worst, frob = assert_score_close(s.cpu().numpy(), s_ref, f"symmetric n={n} d={d}")
+    assert torch.equal(s, P.sdkde_score(xd, h, flags=flags))       # deterministic: no atomics
+    # the fused call takes the same path; its shifted samples carry the score
+    ws = P.make_workspace(n, 8, d, flags=flags)
+    s2 = torch.empty_like(xd)
+    x_sd, _, _ = P.sdkde_fit_eval(xd, torch.from_numpy(q).cuda(), h, score_out=s2, want="both", workspace=ws, flags=flags)
+    assert torch.equal(s2, s)
+    assert_shifted_close(x_sd.cpu().numpy(), oracle.debias(x, s_ref, h), s_ref, h, f"symmetric x_sd n={n} d={d}")
+    print(f"symmetric n={n} d={d}: worst {worst:.3g} of allowance, rel frobenius {frob:.3g}", flush=True)
+
+
+def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib):
+    P, torch = lib
+    sym = P.SDKDE_FLAG_SYMMETRIC
+    for n, m, d, flags in ((3000, 500, 40, 0), (3000, 500, 16, P.SDKDE_PREC_FP16X2), (3000, 500, 2, 0)):
+        print(f"symmetric flag ignored n={n} d={d} flags={flags}", flush=True)
+        assert P.sdkde_describe_plan(n, n, d, 0, flags | sym)["symmetric"] == 0
+        x, q, h = _mixture(n, m, d, 3)
+        xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+        assert torch.equal(P.sdkde_score(xd, h, flags=flags | sym), P.sdkde_score(xd, h, flags=flags))
+    # separate points and eval never take it
+    x, q, h = _mixture(3000, 500, 16, 4)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    assert P.sdkde_describe_plan(3000, 500, 16, 1, sym)["symmetric"] == 0
+    assert torch.equal(P.sdkde_score(xd, h, points=qd, flags=sym), P.sdkde_score(xd, h, points=qd))
+    assert torch.equal(P.sdkde_eval(xd, qd, h, flags=sym)[0], P.sdkde_eval(xd, qd, h)[0])
+
+
 @pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (3000, 777, 1, 0), (2048, 512, 64, 10),
                                         (17, 9, 5, 2)])
 def test_fused_call_matches_oracle_and_three_calls(lib, n, m, d, seed):

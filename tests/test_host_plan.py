@@ -7,7 +7,9 @@ from hypothesis import given, settings, strategies as st
 
 import paper_2602_10378_amd as P
 
-FLAGS = [P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_FLAG_MAX_SHIFT]
+FLAGS = [P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_FLAG_MAX_SHIFT,
+         P.SDKDE_FLAG_SYMMETRIC, P.SDKDE_FLAG_SYMMETRIC | P.SDKDE_PREC_FP16X2,
+         P.SDKDE_FLAG_SYMMETRIC | P.SDKDE_FLAG_MAX_SHIFT]
 
 
 def _check(n, m, d, call, flags):
@@ -47,8 +49,27 @@ def _check(n, m, d, call, flags):
     for (name, off, size), nxt in zip(blocks, blocks[1:] + [("end", p["workspace_bytes"], 0)]):
         assert off % 256 == 0 and off >= 0, name
         assert off + size <= nxt[1], f"{name} overlaps {nxt[0]}"
-    assert p["workspace_bytes"] <= P.sdkde_workspace_bytes(n, m if call else max(m, 1), d, flags & 15 | flags & 16)
+    assert p["workspace_bytes"] <= P.sdkde_workspace_bytes(n, m if call else max(m, 1), d, flags)
+    _check_symmetric(p, n, d, call, flags)
     return p
+
+
+def _check_symmetric(p, n, d, call, flags):
+    """The symmetric mode's decomposition: whole blocks, non-empty groups, LDS within the CU's 160 KiB."""
+    wanted = bool(flags & P.SDKDE_FLAG_SYMMETRIC) and call == 0 and 4 <= d <= 32 and (flags & 15) == 0
+    assert p["symmetric"] == int(wanted)
+    if not wanted:
+        assert p["sym_block_rows"] == p["sym_blocks_per_group"] == p["sym_groups"] == 0
+        return
+    rb, per_group, groups = p["sym_block_rows"], p["sym_blocks_per_group"], p["sym_groups"]
+    rows_held = 8 * 16 * (8 if p["dp"] == 16 else 4)        # rows a workgroup of the symmetric kernel holds
+    assert rb & (rb - 1) == 0 and rb % rows_held == 0 and rb % 256 == 0
+    assert p["n_pad"] % rb == 0 and p["n_pad"] - n < max(rb, 1024)
+    blocks = p["n_pad"] // rb
+    assert 1 <= groups <= 64 and per_group >= 1
+    assert groups * per_group >= blocks > (groups - 1) * per_group
+    assert p["partial_slots"] == groups + 3
+    assert 4 * ((p["dp"] // 16) * rb * 16 + rb + 8 * 16 * 20) <= 160 * 1024
 
 
 @settings(max_examples=300, deadline=None)
@@ -69,6 +90,8 @@ def test_plan_of_the_benchmark_configs(n, m, d):
             assert p["splits"] % 8 == 0                       # one group of splits per XCD
     big = P.sdkde_describe_plan(1048576, 131072, 16, 0)
     assert big["row_tiles"] == 8 and big["splits"] == 8
+    sym = P.sdkde_describe_plan(1048576, 131072, 16, 0, P.SDKDE_FLAG_SYMMETRIC)
+    assert (sym["sym_block_rows"], sym["sym_blocks_per_group"], sym["sym_groups"]) == (2048, 8, 64)
 
 
 def test_describe_plan_rejects_bad_arguments():
