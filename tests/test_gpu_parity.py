@@ -192,9 +192,10 @@ def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
     print(f"symmetric n={n} d={d} env={env} block={plan['sym_block_rows']} per_group={plan['sym_blocks_per_group']} "
           f"groups={plan['sym_groups']}", flush=True)
     assert plan["symmetric"] == 1
-    x, q, h = _mixture(n, 8, d, seed)
-    if n == 1:
-        h = 0.7
+    if n == 1:      # the bandwidth rule needs two samples
+        x, q, h = np.full((1, d), 0.25, np.float32), np.zeros((8, d), np.float32), 0.7
+    else:
+        x, q, h = _mixture(n, 8, d, seed)
     xd = torch.from_numpy(x).cuda()
     s = P.sdkde_score(xd, h, flags=flags)
     s_ref = oracle.score(x, h)
