@@ -1,0 +1,41 @@
+// Types, constants and the kinds of pair kernel shared by every part of the SD-KDE library (gfx950).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <math.h>
+#include <type_traits>
+#include "sdkde.h"
+
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;            // 4 waves per workgroup
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kTile = 16;              // MFMA 16x16x4 tile edge
+constexpr int kRowPad = 1024;          // row padding of every prepared array (>= rows per workgroup)
+constexpr float kPadNorm = -1.0e30f;   // "-|x|^2" of a padding sample: exp2 of it is exactly 0
+constexpr float kPadCoord = 1.0e18f;   // thin-d padding coordinate: squared distance ~1e36, exp2(-that) = 0
+constexpr int kMeanBlocks = 128;
+constexpr int kFlushTiles = 64;         // sample tiles between folds of the running sums (power of two)
+constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3, MFMA path above
+
+// What a pair kernel accumulates.
+enum PairKind {
+    kScoreSelf = 0,     // D and T at the samples themselves (own sample tiles skipped)
+    kScorePoints = 1,   // D and T at separate points
+    kEval = 2,          // D only (Gaussian KDE)
+    kEvalLaplace = 3,   // sum of phi * (1 + d/2 - r^2/2h^2) (Laplace-corrected KDE; signed)
+    kRowMax = 4,        // max_j of the exponent (first pass of the max-shifted mode); kept in the D slot
+    kScoreBand = 5      // as kScoreSelf, but only the samples of the rows' own block (symmetric mode)
+};
+constexpr float kNegHuge = -3.0e38f;
+constexpr float kLn2 = 0.693147180559945309f;
+
+inline int64_t round_up(int64_t v, int64_t q) { return (v + q - 1) / q * q; }
+
+}  // namespace

@@ -1,0 +1,84 @@
+// Pair kernel of the thin path (d <= 3): direct differences on the VALU.
+#pragma once
+#include "common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Main pair kernel, thin-d path (Appendix A: per pair one exp and a handful of ALU ops, no
+// matrix unit).  Each thread owns R evaluation rows; the streamed sample is wave-uniform, so
+// its coordinates come through scalar loads.  Accumulates D_i and, for SCORE, the direct-form
+// numerator N_i = sum_j phi_ij (x~_j - p~_i).  Same grid decomposition as the MFMA kernel with
+// row blocks of kBlock*R rows and "tiles" of 16 samples.
+// ------------------------------------------------------------------------------------------
+template <int D, int R, int KIND>
+__global__ __launch_bounds__(kBlock) void pair_thin_kernel(
+    const float* __restrict__ ps, const float* __restrict__ xs, float* __restrict__ part_t,
+    float* __restrict__ part_d, int ntiles, int tiles_per_split, int nsplit, int64_t m_pad, float laplace_c0,
+    const float* __restrict__ shift)
+{
+    constexpr bool SCORE = KIND == kScoreSelf || KIND == kScorePoints;
+    constexpr bool LAPLACE = KIND == kEvalLaplace;
+    constexpr bool ROWMAX = KIND == kRowMax;
+    const int split = blockIdx.x % nsplit;
+    const int64_t row_block = blockIdx.x / nsplit;
+    const int64_t row0 = row_block * (kBlock * R) + threadIdx.x;
+
+    // sh[q]: the row's shift (max_j of -r^2, <= 0) in the max-shifted mode, else 0; the squared distance is
+    // accumulated on top of it so that exp2(-(r^2 + sh)) = phi / 2^sh costs no extra instruction.
+    float p[R][D], dacc[R], nacc[R][SCORE ? D : 1], sh[R];
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+#pragma unroll
+        for (int k = 0; k < D; ++k) p[q][k] = ps[(row0 + (int64_t)q * kBlock) * D + k];
+        sh[q] = (!ROWMAX && shift) ? shift[row0 + (int64_t)q * kBlock] : 0.0f;
+        dacc[q] = ROWMAX ? kNegHuge : 0.0f;
+#pragma unroll
+        for (int k = 0; k < (SCORE ? D : 1); ++k) nacc[q][k] = 0.0f;
+    }
+
+    const int t_begin = split * tiles_per_split;
+    const int t_end = min(ntiles, t_begin + tiles_per_split);
+    for (int jt = t_begin; jt < t_end; ++jt) {
+        const float* xj = xs + (int64_t)jt * kTile * D;    // wave-uniform address
+#pragma unroll
+        for (int jj = 0; jj < kTile; ++jj) {
+            float xv[D];
+#pragma unroll
+            for (int k = 0; k < D; ++k) xv[k] = xj[jj * D + k];
+#pragma unroll
+            for (int q = 0; q < R; ++q) {
+                float diff[D];
+                float r2 = sh[q];
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    diff[k] = xv[k] - p[q][k];
+                    r2 = fmaf(diff[k], diff[k], r2);
+                }
+                if (ROWMAX) {
+                    dacc[q] = fmaxf(dacc[q], -r2);
+                    continue;
+                }
+                float phi = __builtin_amdgcn_exp2f(-r2);
+                // Laplace factor 1 + d/2 - r^2/2h^2, with the true r^2 = r2 - sh
+                if (LAPLACE) dacc[q] = fmaf(phi, fmaf(sh[q] - r2, kLn2, laplace_c0), dacc[q]);
+                else dacc[q] += phi;
+                if (SCORE) {
+#pragma unroll
+                    for (int k = 0; k < D; ++k) nacc[q][k] = fmaf(phi, diff[k], nacc[q][k]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < R; ++q) {
+        const int64_t row = row0 + (int64_t)q * kBlock;
+        part_d[(int64_t)split * m_pad + row] = dacc[q];
+        if (SCORE) {
+#pragma unroll
+            for (int k = 0; k < D; ++k) part_t[((int64_t)split * m_pad + row) * D + k] = nacc[q][k];
+        }
+    }
+}
+
+}  // namespace

@@ -1,0 +1,152 @@
+// Prep kernels: column means, then centre + scale + pad (+ fp16 hi/lo split) into the layouts the pair kernels read.
+#pragma once
+#include "common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Prep: column means (deterministic two-stage reduction), then centre + scale + pad.
+// ------------------------------------------------------------------------------------------
+
+// partial[b][c] = sum over this block's rows of x[row][c], double accumulation.
+__global__ __launch_bounds__(kBlock) void mean_partial_kernel(const float* __restrict__ x, int64_t n,
+                                                              int d, double* __restrict__ partial)
+{
+    __shared__ double red[kBlock];
+    const int rows_per_iter = kBlock / d;              // d <= 128 < kBlock
+    const int rr = threadIdx.x / d, c = threadIdx.x % d;
+    double acc = 0.0;
+    if (rr < rows_per_iter) {
+        for (int64_t row = (int64_t)blockIdx.x * rows_per_iter + rr; row < n;
+             row += (int64_t)gridDim.x * rows_per_iter)
+            acc += (double)x[row * d + c];
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < d) {
+        double s = 0.0;
+        for (int r = 0; r < rows_per_iter; ++r) s += red[r * d + threadIdx.x];
+        partial[(int64_t)blockIdx.x * d + threadIdx.x] = s;
+    }
+}
+
+// Second stage of the column mean, done by every prep workgroup for itself (saves a launch):
+// sums the kMeanBlocks partials of each column in a fixed order, so all workgroups get the same
+// bits.  Result in smean[0 .. d); ends with a barrier.
+__device__ __forceinline__ void block_mean(const double* __restrict__ partial, int d, int64_t n, double* red,
+                                           float* smean)
+{
+    const int slices = kBlock / d;                        // d <= 128, so >= 2
+    const int sl = threadIdx.x / d, c = threadIdx.x % d;
+    double acc = 0.0;
+    if (sl < slices)
+        for (int b = sl; b < kMeanBlocks; b += slices) acc += partial[(int64_t)b * d + c];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < d) {
+        double t = 0.0;
+        for (int q = 0; q < slices; ++q) t += red[q * d + threadIdx.x];
+        smean[threadIdx.x] = (float)(t / (double)n);
+    }
+    __syncthreads();
+}
+
+// One array to prepare: src[rows][d] -> dst (rows_pad rows), optional blocked transpose dst_t, norms dst_n.
+struct PrepJob {
+    const float* src;
+    int64_t rows, rows_pad;
+    float* dst;
+    float* dst_t;
+    float* dst_n;
+    float pad_value;      // thin path only: coordinate value of padding rows
+};
+
+constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (two 16-sample tiles; 2 x 16.5 KiB of LDS)
+
+// Centre, scale and pad for the MFMA path.  A workgroup stages kPrepRows rows in LDS and writes
+//   dst[row][dp]   = a (x - mean), 0 in padding columns and rows (coalesced row writes),
+//   dst_t[row/16][col][row%16] = the same values with each 16-sample tile transposed (if dst_t),
+//   dst_n[row]     = -|dst[row]|^2 in double, rounded once; kPadNorm for padding rows.
+// prec >= SDKDE_PREC_FP16X2 (fp16x2 input modes): dst holds, per 16-column block, 16 fp16 "hi" values
+// followed by 16 fp16 "lo" values with hi + lo = the fp32 coordinate to ~22 mantissa bits (same bytes
+// per row as fp32); the norm is then taken of hi + lo so that it matches what the MFMA multiplies.
+// prec == SDKDE_PREC_FP16X2_ALL: dst_t holds fp16 pairs too, laid out as the A operand of the K = 32
+// second contraction: for tile, column c and lane group g, eight halves [hi(4g..4g+3) | the same again]
+// followed by eight halves [lo(4g..4g+3) | the same again] (twice the bytes of the fp32 layout).
+// Grid: job0's blocks first (blocks0 of them), then job1's; sample mean from mean_partial.
+__global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
+                                                           const double* __restrict__ mean_partial, int64_t n_mean,
+                                                           float a, int prec)
+{
+    __shared__ double red[kBlock];
+    __shared__ float smean[SDKDE_MAX_D];
+    __shared__ float raw[kPrepRows][SDKDE_MAX_D + 1];     // a (x - mean)
+    __shared__ float used[kPrepRows][SDKDE_MAX_D + 1];    // the value the first contraction multiplies (hi + lo, or raw)
+    block_mean(mean_partial, d, n_mean, red, smean);
+
+    const bool second = (int)blockIdx.x >= blocks0;
+    const PrepJob& job = second ? job1 : job0;
+    const int64_t r0 = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kPrepRows;
+    _Float16* dst_h = reinterpret_cast<_Float16*>(job.dst);
+
+    for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
+        const int rr = idx / dp, c = idx % dp;
+        const int64_t row = r0 + rr;
+        float v = 0.0f;
+        if (row < job.rows && c < d) v = a * (job.src[row * d + c] - smean[c]);
+        raw[rr][c] = v;
+        if (prec != SDKDE_PREC_FP32) {
+            const _Float16 hi = (_Float16)v;
+            const _Float16 lo = (_Float16)(v - (float)hi);
+            _Float16* out = dst_h + row * 2 * dp + (c / 16) * 32 + (c % 16);
+            out[0] = hi;
+            out[16] = lo;
+            v = (float)hi + (float)lo;
+        } else {
+            job.dst[row * dp + c] = v;
+        }
+        used[rr][c] = v;
+    }
+    __syncthreads();
+    if (job.dst_t && prec != SDKDE_PREC_FP16X2_ALL) {
+        float* base = job.dst_t + (r0 / kTile) * (int64_t)dp * kTile;
+        for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
+            const int tile = idx / (dp * kTile), c = (idx / kTile) % dp, rr = idx % kTile;
+            base[idx] = raw[tile * kTile + rr][c];        // idx = (tile*dp + c)*16 + rr
+        }
+    } else if (job.dst_t) {
+        _Float16* base = reinterpret_cast<_Float16*>(job.dst_t) + (r0 / kTile) * (int64_t)dp * 64;
+        for (int idx = threadIdx.x; idx < kPrepRows * dp * 4; idx += kBlock) {
+            // idx = ((tile*dp + c)*4 + g)*16 + e
+            const int e = idx % 16, g = (idx / 16) % 4, c = (idx / 64) % dp, tile = idx / (64 * dp);
+            const float v = raw[tile * kTile + 4 * g + (e & 3)][c];
+            const _Float16 hi = (_Float16)v;
+            base[idx] = e < 8 ? hi : (_Float16)(v - (float)hi);
+        }
+    }
+    if (threadIdx.x < kPrepRows) {
+        double acc = 0.0;
+        for (int c = 0; c < dp; ++c) acc += (double)used[threadIdx.x][c] * (double)used[threadIdx.x][c];
+        const int64_t row = r0 + threadIdx.x;
+        job.dst_n[row] = row < job.rows ? -(float)acc : kPadNorm;
+    }
+}
+
+// Thin-d variant: dst[row][d] = a (x - mean), padding rows get pad_value in every coordinate.
+// One thread per padded row; same two-job grid.
+__global__ __launch_bounds__(kBlock) void prep_thin_kernel(PrepJob job0, PrepJob job1, int blocks0, int d,
+                                                           const double* __restrict__ mean_partial, int64_t n_mean,
+                                                           float a)
+{
+    __shared__ double red[kBlock];
+    __shared__ float smean[SDKDE_MAX_D];
+    block_mean(mean_partial, d, n_mean, red, smean);
+    const bool second = (int)blockIdx.x >= blocks0;
+    const PrepJob& job = second ? job1 : job0;
+    const int64_t row = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kBlock + threadIdx.x;
+    if (row >= job.rows_pad) return;
+    for (int c = 0; c < d; ++c)
+        job.dst[row * d + c] = row < job.rows ? a * (job.src[row * d + c] - smean[c]) : job.pad_value;
+}
+
+}  // namespace

@@ -9,23 +9,24 @@ import sdkde_inputs
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,n,m", [("C1", 4096, 1024), ("C3", 5000, 700)])
-def test_pipeline_replays_from_a_graph(name, n, m):
+@pytest.mark.parametrize("name,n,m,flags", [("C1", 4096, 1024, 0), ("C3", 5000, 700, 0), ("C1", 5000, 700, 32)])
+def test_pipeline_replays_from_a_graph(name, n, m, flags):
     import torch
     import paper_2602_10378_amd as P
+    print(f"graph {name} n={n} m={m} flags={flags}", flush=True)
     x, q, h = sdkde_inputs.make(name, seed=0, n=n, m=m)
     d = x.shape[1]
     xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
-    ws = P.make_workspace(n, m, d)
+    ws = P.make_workspace(n, m, d, flags=flags)        # 32 = SDKDE_FLAG_SYMMETRIC: the score's symmetric mode
     s = torch.empty_like(xd)
     x_sd = torch.empty_like(xd)
     dens = torch.empty(m, device="cuda")
     logd = torch.empty(m, device="cuda")
 
     def step():
-        P.sdkde_score(xd, h, out=s, workspace=ws)
+        P.sdkde_score(xd, h, out=s, workspace=ws, flags=flags)
         P.sdkde_debias(xd, s, h, out=x_sd)
-        P.sdkde_eval(x_sd, qd, h, density_out=dens, log_density_out=logd, workspace=ws)
+        P.sdkde_eval(x_sd, qd, h, density_out=dens, log_density_out=logd, workspace=ws, flags=flags)
 
     step()
     torch.cuda.synchronize()
