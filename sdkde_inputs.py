@@ -109,6 +109,20 @@ def true_log_density(q, weights, means, variances) -> np.ndarray:
     return top + np.log(np.exp(logs - top).sum(0))
 
 
+def standard_normal_cloud(rows: int, d: int, seed: int = 0, scale: float = 1.0) -> np.ndarray:
+    """rows x d fp32 draws of N(0, scale^2), generated in fp32 chunk by chunk (for arrays too large to
+    go through float64): the index-range tests use it for hundreds of millions of rows."""
+    rng = np.random.default_rng(seed)
+    out = np.empty((rows, d), dtype=np.float32)
+    step = 1 << 22
+    for lo in range(0, rows, step):
+        hi = min(rows, lo + step)
+        out[lo:hi] = rng.standard_normal((hi - lo, d), dtype=np.float32)
+    if scale != 1.0:
+        out *= np.float32(scale)
+    return out
+
+
 def make(name: str, seed: int = 0, n: int | None = None, m: int | None = None):
     """Inputs of a named config; n/m may be overridden to get a scaled-down case of the
     same distribution."""
