@@ -225,6 +225,14 @@ def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib):
     assert P.sdkde_describe_plan(3000, 500, 16, 1, sym)["symmetric"] == 0
     assert torch.equal(P.sdkde_score(xd, h, points=qd, flags=sym), P.sdkde_score(xd, h, points=qd))
     assert torch.equal(P.sdkde_eval(xd, qd, h, flags=sym)[0], P.sdkde_eval(xd, qd, h)[0])
+    # where it applies it needs its own, larger workspace: one sized for the ordinary path is refused
+    n_big = 40000
+    xb = torch.from_numpy(_mixture(n_big, 8, 16, 5)[0]).cuda()
+    small = torch.empty(P.sdkde_workspace_bytes(n_big, 8, 16, P.SDKDE_PREC_FP16X2_ALL), dtype=torch.uint8, device="cuda")
+    assert P.sdkde_workspace_bytes(n_big, 8, 16, sym) > small.numel()
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_score(xb, 1.0, workspace=small, flags=sym)
+    assert e.value.status == 3
 
 
 @pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (3000, 777, 1, 0), (2048, 512, 64, 10),
