@@ -165,7 +165,15 @@ def main():
                            "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                            "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get(args.config) if (args.n is None and args.m is None) else None,
                            "kernel": "pair_mfma_kernel (score)", "launch_ms": score_avg_ms,
-                           "flops_per_launch": score_flops}
+                           "flops_per_launch": score_flops,
+                           # per 16 x 16 tile of pairs: 8 d/16 MFMAs of 32 clocks, and 4 v_exp_f32 + 8 v_add_f32 that
+                           # cannot overlap them (fp32 MFMA and VALU do not co-issue on gfx950; measured by sdkde_peaks:
+                           # profiles/peaks_fp32_mfma_valu_coissue.txt, which times this mix at 333 clocks for d = 16:
+                           # 256 + 64 + 13 of switching between the two): the share of the time the MFMA pipe can have
+                           "frac_ceiling_of_instruction_mix": (256.0 * d / 16) / (256.0 * d / 16 + 4 * 8 + 8 * 4 + 13),
+                           "valu": {"exp_per_s": float(n) * n / (score_avg_ms * 1e-3),
+                                    "peak_exp_per_s": 256 * 4 * 16 * 2.4e9 / 2.0,
+                                    "note": "v_exp_f32 at half rate (8 clocks per wave instruction); sdkde_peaks measures 14.8e12/s back to back"}}
     else:
         # thin-d path (Appendix A): VALU-issue bound.  Per score pair: d subs + d FMAs (r^2) + 1 add (D) + d FMAs
         # (numerator) + one v_exp_f32, which issues at half rate (2 slots).  Peak = 256 CUs x 4 SIMDs x 16 lanes x
