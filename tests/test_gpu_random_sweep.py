@@ -28,7 +28,7 @@ def _cases(count, seed):
         yield k, n, m, d, comps, data_seed, diag, factor, flags
 
 
-@pytest.mark.parametrize("seed", [2024, 7])
+@pytest.mark.parametrize("seed", [2024, 7, 11])
 def test_random_sweep_matches_oracle(seed):
     import torch
     import paper_2602_10378_amd as P
@@ -43,7 +43,16 @@ def test_random_sweep_matches_oracle(seed):
         sp = P.sdkde_score(xd, h, points=qd, flags=flags).cpu().numpy()
         logd = P.sdkde_eval(xd, qd, h, want="log", flags=flags)[1].cpu().numpy()
         assert np.all(np.isfinite(s)) and np.all(np.isfinite(sp))
-        e_self, _ = score_error(s, oracle.score(x, h))
+        s_ref = oracle.score(x, h)
+        if (flags & 15) == 2:
+            # the fp16 split of Phi resolves weights to 2^-39 of the sample's own unit weight (header, FP16X2_ALL):
+            # the stated absolute term on top of the relative allowance
+            ref = np.linalg.norm(s_ref, axis=1)
+            allow = TOL * np.maximum(ref, 1e-3 * np.sqrt(np.mean(ref**2)))
+            allow += n * 2.0**-39 * np.linalg.norm(x - x.mean(0), axis=1).max() / h**2
+            e_self = float(np.max(np.linalg.norm(s.astype(np.float64) - s_ref, axis=1) / allow))
+        else:
+            e_self, _ = score_error(s, s_ref)
         # separate points: where the sums do not underflow in fp32 (documented), everywhere with the max shift
         keep = np.ones(m, bool) if flags & 16 else np.isfinite(logd)
         if flags & 16:
