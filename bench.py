@@ -97,11 +97,15 @@ def main():
         step()
     torch.cuda.synchronize()
     P.sdkde_profile_enable(True)      # HIP events around the main kernels, on the stream they run on
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # per-step spread (same stream)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for k in range(args.steps):
         step()
+        marks[k + 1].record()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    per_step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
     score_launches, score_ms = P.sdkde_profile_summary(0)
     eval_launches, eval_ms = P.sdkde_profile_summary(1)
     P.sdkde_profile_enable(False)
@@ -157,6 +161,8 @@ def main():
         "config": {"workload": f"{cfg.name}: n={n} samples, m={m} queries, d={d}, Gaussian mixture, "
                                f"Silverman h={h:.4f}, score+debias+eval", "n": n, "m": m, "d": d, "seed": args.seed},
         "end_to_end_s": dt / args.steps,
+        "ms_per_step_min": per_step_ms[0] if per_step_ms else None,
+        "ms_per_step_median": per_step_ms[len(per_step_ms) // 2] if per_step_ms else None,
         "stages_ms": {"score_main_kernel": score_avg_ms, "eval_main_kernel": eval_avg_ms,
                       "everything_else": ms_per_step - score_avg_ms - eval_avg_ms},
     }
