@@ -23,7 +23,7 @@ __global__ __launch_bounds__(kBlock) void mean_partial_kernel(const float* __res
     }
     red[threadIdx.x] = acc;
     __syncthreads();
-    if (threadIdx.x < d) {
+    if ((int)threadIdx.x < d) {
         double s = 0.0;
         for (int r = 0; r < rows_per_iter; ++r) s += red[r * d + threadIdx.x];
         partial[(int64_t)blockIdx.x * d + threadIdx.x] = s;
@@ -43,7 +43,7 @@ __device__ __forceinline__ void block_mean(const double* __restrict__ partial, i
         for (int b = sl; b < kMeanBlocks; b += slices) acc += partial[(int64_t)b * d + c];
     red[threadIdx.x] = acc;
     __syncthreads();
-    if (threadIdx.x < d) {
+    if ((int)threadIdx.x < d) {
         double t = 0.0;
         for (int q = 0; q < slices; ++q) t += red[q * d + threadIdx.x];
         smean[threadIdx.x] = (float)(t / (double)n);
