@@ -174,7 +174,7 @@ def main():
                            "flops_per_launch": score_flops,
                            # per 16 x 16 tile of pairs: 8 d/16 MFMAs of 32 clocks, and 4 v_exp_f32 + 8 v_add_f32 that
                            # cannot overlap them (fp32 MFMA and VALU do not co-issue on gfx950; measured by sdkde_peaks:
-                           # profiles/peaks_fp32_mfma_valu_coissue.txt, which times this mix at 333 clocks for d = 16:
+                           # profiles/peaks_mfma_valu_coissue.txt, which times this mix at 333 clocks for d = 16:
                            # 256 + 64 + 13 of switching between the two): the share of the time the MFMA pipe can have
                            "frac_ceiling_of_instruction_mix": (256.0 * d / 16) / (256.0 * d / 16 + 4 * 8 + 8 * 4 + 13),
                            "valu": {"exp_per_s": float(n) * n / (score_avg_ms * 1e-3),

@@ -1,12 +1,15 @@
 // sdkde_peaks: measures, on the GPU it runs on, the instruction rates the SD-KDE pair kernels are
 // bounded by: fp32 MFMA (16x16x4 and 32x32x2), v_exp_f32, v_fma_f32, and how fp32 MFMA and VALU
-// work share a SIMD (NM MFMAs per iteration with NE exps and NA adds, all mutually independent).
+// work share a SIMD (NM MFMAs per iteration with NE exps and NA adds, all mutually independent), and
+// the same for the fp16 MFMAs of the lower-precision input modes.
 // Cycle figures assume the nominal 2.4 GHz engine clock.
 #include <hip/hip_runtime.h>
 #include <cstdio>
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 namespace {
 
@@ -97,6 +100,39 @@ __global__ __launch_bounds__(kBlock) void mix_kernel(float* out, int iters, floa
     out[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
+// fp16 MFMAs: K32 ? v_mfma_f32_16x16x32_f16 : v_mfma_f32_16x16x16_f16; NM of them, then NE exps and NA adds as one clump.
+template <bool K32, int NM, int NE, int NA>
+__global__ __launch_bounds__(kBlock) void mix_f16_kernel(float* out, int iters, float a, float b)
+{
+    f32x4 acc[4];
+    float e[8], s[8];
+    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0, 0, 0, 0};
+    for (int c = 0; c < 8; ++c) {
+        e[c] = -0.001f * (threadIdx.x + c);
+        s[c] = c;
+    }
+    const _Float16 ha = (_Float16)a, hb = (_Float16)b;
+    const f16x4 a4 = {ha, hb, ha, hb};
+    const f16x8 a8 = {ha, hb, ha, hb, ha, hb, ha, hb};
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int k = 0; k < NM; ++k) {
+            if (K32) acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, a8, acc[k % 4], 0, 0, 0);
+            else acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x16f16(a4, a4, acc[k % 4], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < NE; ++q) e[q % 8] = __builtin_amdgcn_exp2f(e[q % 8]);
+#pragma unroll
+        for (int q = 0; q < NA; ++q) s[q % 8] = s[q % 8] + a;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float r = 0;
+    for (int c = 0; c < 4; ++c) r += acc[c].x + acc[c].y + acc[c].z + acc[c].w;
+    for (int c = 0; c < 8; ++c) r += e[c] + s[c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
 hipEvent_t g_e0, g_e1;
 float* g_out;
 
@@ -124,6 +160,18 @@ void run_mix(int waves_per_simd)
     const double tflops = NM * 32.0 * kIters * (double)blocks * kBlock / (ms * 1e-3) / 1e12;
     printf("  %d MFMA + %2d exp + %2d add, %-11s %d waves/SIMD: %6.1f clk per iteration per wave, MFMA %6.1f TFLOP/s\n", NM,
            NE, NA, SPREAD ? "interleaved" : "one clump", waves_per_simd, clk, tflops);
+}
+
+template <bool K32, int NM, int NE, int NA>
+void run_mix_f16(int waves_per_simd)
+{
+    const int blocks = kCUs * waves_per_simd;
+    float ms = time_ms([&] {
+        hipLaunchKernelGGL((mix_f16_kernel<K32, NM, NE, NA>), dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 1.0f, 0.5f);
+    });
+    const double clk = ms * 1e-3 * kClockHz / kIters / waves_per_simd;
+    printf("  %d x %s + %2d exp + %2d add, one clump, %d waves/SIMD: %6.1f clk per iteration per wave\n", NM,
+           K32 ? "16x16x32_f16" : "16x16x16_f16", NE, NA, waves_per_simd, clk);
 }
 
 }  // namespace
@@ -162,6 +210,15 @@ int main()
         run_mix<8, 4, 8, true>(w);
         run_mix<8, 4, 8, false>(w);
         run_mix<8, 8, 16, false>(w);
+    }
+
+    printf("fp16 MFMA and VALU on one SIMD (the 16x16x16 and 16x16x32 forms take the same time per instruction):\n");
+    for (int w : {2, 4}) {
+        run_mix_f16<false, 8, 0, 0>(w);
+        run_mix_f16<true, 8, 0, 0>(w);
+        run_mix_f16<true, 0, 8, 8>(w);
+        run_mix_f16<true, 4, 8, 8>(w);
+        run_mix_f16<true, 4, 4, 16>(w);
     }
     return 0;
 }
