@@ -126,3 +126,35 @@ def test_max_shift_mode_handles_points_whose_weights_all_underflow(d):
     # and the fp16x2 input mode composes with it
     _, c = P.sdkde_eval(xd, qd, h, want="log", flags=flags | P.SDKDE_PREC_FP16X2)
     assert_log_density_close(c.cpu().numpy(), ref, f"shifted fp16x2 eval d={d}")
+
+
+def test_profile_instrumentation_counts_launches_on_the_callers_stream():
+    """sdkde_profile_enable / sdkde_profile_summary: one record per call and kind, on whatever stream the call was
+    given, with durations that agree with stream events placed around the same calls."""
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    print("profile instrumentation", flush=True)
+    x, q, h = sdkde_inputs.make("C1", seed=0, n=20000, m=3000)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ws = P.make_workspace(20000, 3000, 16)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    P.sdkde_score(xd, h, workspace=ws)                 # warm-up, not recorded
+    torch.cuda.synchronize()
+    P.sdkde_profile_enable(True)
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(side):
+        t0.record()
+        for _ in range(3):
+            P.sdkde_score(xd, h, workspace=ws)
+        t1.record()
+        P.sdkde_eval(xd, qd, h, workspace=ws)
+    torch.cuda.synchronize()
+    n_score, ms_score = P.sdkde_profile_summary(0)
+    n_eval, ms_eval = P.sdkde_profile_summary(1)
+    P.sdkde_profile_enable(False)
+    assert (n_score, n_eval) == (3, 1)
+    assert 0.0 < ms_score <= t0.elapsed_time(t1) and ms_eval > 0.0
+    assert ms_score > 0.5 * t0.elapsed_time(t1)        # the pair kernel dominates a call of this size
+    assert P.sdkde_profile_summary(0) == (0, 0.0)      # disabling reset the record
