@@ -26,6 +26,9 @@
  *    arguments give bit-identical outputs.
  *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
  *    are unspecified.  Two calls that share a workspace must be ordered on one stream.
+ *  - Host threads: calls keep no state between them (the optional instrumentation below aside), so
+ *    several threads may call concurrently, each with its own workspace and stream, on the device that is
+ *    current in that thread.
  */
 #ifndef SDKDE_H
 #define SDKDE_H
