@@ -158,3 +158,45 @@ def test_profile_instrumentation_counts_launches_on_the_callers_stream():
     assert 0.0 < ms_score <= t0.elapsed_time(t1) and ms_eval > 0.0
     assert ms_score > 0.5 * t0.elapsed_time(t1)        # the pair kernel dominates a call of this size
     assert P.sdkde_profile_summary(0) == (0, 0.0)      # disabling reset the record
+
+
+def test_concurrent_host_threads_with_their_own_streams():
+    """Several host threads, each with its own workspace and stream, get the same bits as a lone call."""
+    import threading
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    print("concurrent host threads", flush=True)
+    cases = []
+    for k, (n, m, d, flags) in enumerate([(6000, 800, 16, 0), (5000, 700, 20, 1), (7000, 900, 16, 32), (4000, 600, 2, 0)]):
+        x, q, h = (sdkde_inputs.mixture_1d(n, m, 20 + k) if d == 1 else
+                   sdkde_inputs.gaussian_mixture(n, m, d, 3, seed=20 + k))
+        xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+        want_s = P.sdkde_score(xd, h, flags=flags)
+        want_p = P.sdkde_eval(xd, qd, h, want="log", flags=flags)[1]
+        cases.append((xd, qd, h, flags, want_s, want_p))
+    torch.cuda.synchronize()
+    failures = []
+
+    def worker(case):
+        xd, qd, h, flags, want_s, want_p = case
+        try:
+            stream = torch.cuda.Stream()
+            ws = P.make_workspace(xd.shape[0], qd.shape[0], xd.shape[1], flags=flags)
+            with torch.cuda.stream(stream):
+                for _ in range(5):
+                    s = P.sdkde_score(xd, h, workspace=ws, flags=flags, stream=stream)
+                    p = P.sdkde_eval(xd, qd, h, want="log", workspace=ws, flags=flags, stream=stream)[1]
+            stream.synchronize()
+            if not (torch.equal(s, want_s) and torch.equal(p, want_p)):
+                failures.append("result differs")
+        except Exception as e:       # noqa: BLE001 - reported below, from the main thread
+            failures.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(c,)) for c in cases]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads)
+    assert not failures, failures
