@@ -166,7 +166,7 @@ def main():
         "stages_ms": {"score_main_kernel": score_avg_ms, "eval_main_kernel": eval_avg_ms,
                       "everything_else": ms_per_step - score_avg_ms - eval_avg_ms},
     }
-    if d > 3:
+    if not P.sdkde_describe_plan(n, n, d, 0)["thin"]:
         out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
                            "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get(args.config) if (args.n is None and args.m is None) else None,

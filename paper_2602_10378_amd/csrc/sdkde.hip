@@ -77,11 +77,14 @@ int env_int(const char* name, int fallback)
 // Workgroups needed to keep 256 CUs busy with a few waves per SIMD.
 constexpr int64_t kTargetBlocks = 2048;
 
-Plan make_plan(int64_t n, int64_t m, int d, bool score)
+Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
 {
     Plan p{};
     p.d = d;
-    p.thin = d <= kThinMaxD;
+    // Direct differences on the VALU beat a zero-padded K = 16 contraction up to d = 5 with fp32 inputs (measured at
+    // n = 262144: score 25.5 / 29.2 ms at d = 4 / 5 against 36.3 ms, eval 4.6 / 5.2 against 5.5 ms; slower from
+    // d = 6 for eval, d = 7 for the score); with fp16 matrix inputs the matrix path wins from d = 4.
+    p.thin = d <= kThinMaxD || (d <= kThinMaxDFp32 && (flags & 15u) == SDKDE_PREC_FP32);
     p.dp = p.thin ? d : (int)round_up(d, 16);
     p.n_pad = round_up(n, kRowPad);
     p.m_pad = round_up(m > 0 ? m : 1, kRowPad);
@@ -285,6 +288,12 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
             case 34: SDKDE_LAUNCH_THIN(3, 4); break;
             case 32: SDKDE_LAUNCH_THIN(3, 2); break;
             case 31: SDKDE_LAUNCH_THIN(3, 1); break;
+            case 44: SDKDE_LAUNCH_THIN(4, 4); break;
+            case 42: SDKDE_LAUNCH_THIN(4, 2); break;
+            case 41: SDKDE_LAUNCH_THIN(4, 1); break;
+            case 54: SDKDE_LAUNCH_THIN(5, 4); break;
+            case 52: SDKDE_LAUNCH_THIN(5, 2); break;
+            case 51: SDKDE_LAUNCH_THIN(5, 1); break;
             default: return SDKDE_EUNSUPPORTED;
         }
     } else {
@@ -474,7 +483,7 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
     flags = anchored_flags(flags, self);
 
-    Plan p = make_plan(n, m, d, true);
+    Plan p = make_plan(n, m, d, true, flags);
     apply_symmetric(p, n, flags, self);
     const Workspace w = layout(p, true, !self, workspace, flags);
     if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
@@ -520,7 +529,7 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if (!queries || (!density_out && !log_density_out)) return SDKDE_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
 
-    const Plan p = make_plan(n, m, d, false);
+    const Plan p = make_plan(n, m, d, false, flags);
     const Workspace w = layout(p, false, true, workspace, flags);
     if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
@@ -556,13 +565,13 @@ int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_
     int rc = check_common(bytes, n, m, d, 1.0, flags);
     if (rc != SDKDE_OK) return rc;
     // Largest of: score at the samples themselves, score at m separate points, eval at m queries.
-    Plan self_plan = make_plan(n, n, d, true);
+    Plan self_plan = make_plan(n, n, d, true, flags);
     apply_symmetric(self_plan, n, flags, true);
     size_t need = layout(self_plan, true, false, nullptr, flags).bytes;
     if (m > 0) {
-        size_t b = layout(make_plan(n, m, d, true), true, true, nullptr, flags).bytes;
+        size_t b = layout(make_plan(n, m, d, true, flags), true, true, nullptr, flags).bytes;
         need = b > need ? b : need;
-        b = layout(make_plan(n, m, d, false), false, true, nullptr, flags).bytes;
+        b = layout(make_plan(n, m, d, false, flags), false, true, nullptr, flags).bytes;
         need = b > need ? b : need;
     }
     *bytes = need;
@@ -627,7 +636,7 @@ int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t 
     const bool separate = call != 0;
     const int64_t rows = call == 0 ? n : m;
     if (score) flags = anchored_flags(flags, !separate);
-    Plan p = make_plan(n, rows, d, score);
+    Plan p = make_plan(n, rows, d, score, flags);
     if (score) apply_symmetric(p, n, flags, !separate);
     char* const base = reinterpret_cast<char*>(uintptr_t(1) << 20);      // any aligned non-null address: offsets only
     const Workspace w = layout(p, score, separate, base, flags);
