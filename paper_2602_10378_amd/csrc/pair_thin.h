@@ -26,20 +26,39 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
 
     // sh[q]: the row's shift (max_j of -r^2, <= 0) in the max-shifted mode, else 0; the squared distance is
     // accumulated on top of it so that exp2(-(r^2 + sh)) = phi / 2^sh costs no extra instruction.
-    float p[R][D], dacc[R], nacc[R][SCORE ? D : 1], sh[R];
+    // Two-level accumulation as in the matrix path: the running sums are folded into (dsum, nsum) every
+    // kFlushTiles sample tiles, so that no fp32 accumulator sees a long chain of additions at its own magnitude.
+    float p[R][D], dacc[R], nacc[R][SCORE ? D : 1], dsum[R], nsum[R][SCORE ? D : 1], sh[R];
 #pragma unroll
     for (int q = 0; q < R; ++q) {
 #pragma unroll
         for (int k = 0; k < D; ++k) p[q][k] = ps[(row0 + (int64_t)q * kBlock) * D + k];
         sh[q] = (!ROWMAX && shift) ? shift[row0 + (int64_t)q * kBlock] : 0.0f;
-        dacc[q] = ROWMAX ? kNegHuge : 0.0f;
+        dacc[q] = dsum[q] = ROWMAX ? kNegHuge : 0.0f;
 #pragma unroll
-        for (int k = 0; k < (SCORE ? D : 1); ++k) nacc[q][k] = 0.0f;
+        for (int k = 0; k < (SCORE ? D : 1); ++k) nacc[q][k] = nsum[q][k] = 0.0f;
     }
+    auto fold = [&]() {
+#pragma unroll
+        for (int q = 0; q < R; ++q) {
+            if (ROWMAX) {
+                dsum[q] = fmaxf(dsum[q], dacc[q]);
+            } else {
+                dsum[q] += dacc[q];
+                dacc[q] = 0.0f;
+            }
+#pragma unroll
+            for (int k = 0; k < (SCORE ? D : 1); ++k) {
+                nsum[q][k] += nacc[q][k];
+                nacc[q][k] = 0.0f;
+            }
+        }
+    };
 
     const int t_begin = split * tiles_per_split;
     const int t_end = min(ntiles, t_begin + tiles_per_split);
     for (int jt = t_begin; jt < t_end; ++jt) {
+        if (((jt - t_begin) & (kFlushTiles - 1)) == kFlushTiles - 1) fold();
         const float* xj = xs + (int64_t)jt * kTile * D;    // wave-uniform address
 #pragma unroll
         for (int jj = 0; jj < kTile; ++jj) {
@@ -70,13 +89,14 @@ __global__ __launch_bounds__(kBlock) void pair_thin_kernel(
             }
         }
     }
+    fold();
 #pragma unroll
     for (int q = 0; q < R; ++q) {
         const int64_t row = row0 + (int64_t)q * kBlock;
-        part_d[(int64_t)split * m_pad + row] = dacc[q];
+        part_d[(int64_t)split * m_pad + row] = dsum[q];
         if (SCORE) {
 #pragma unroll
-            for (int k = 0; k < D; ++k) part_t[((int64_t)split * m_pad + row) * D + k] = nacc[q][k];
+            for (int k = 0; k < D; ++k) part_t[((int64_t)split * m_pad + row) * D + k] = nsum[q][k];
         }
     }
 }
