@@ -15,11 +15,11 @@
  *  - h is passed as double so that the derived constants are formed in double and rounded
  *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation) unless
  *    `flags` selects another input mode.
- *  - Accuracy domain of the matrix path (d >= 6, and d = 4, 5 with fp16 matrix inputs): squared distances are formed as
+ *  - Accuracy domain of the matrix path (d >= 4): squared distances are formed as
  *    |p|^2 + |x|^2 - 2 p.x on mean-centred coordinates, which loses about (R/h)^2 * 2^-24 in
  *    the exponent of phi (R = distance of a point from the sample mean).  The stated 1e-3
- *    tolerances hold while R/h stays below ~100; the thin path (d <= 3, and d <= 5 with
- *    SDKDE_PREC_FP32) uses direct differences and has no such limit.  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
+ *    tolerances hold while R/h stays below ~100; the thin path (d <= 3) uses direct
+ *    differences and has no such limit.  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
  *    is kept: a point at which every phi_j is below the fp32 range (exponent under -126 ln 2)
  *    gets the documented all-underflow results instead of a shifted sum.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
@@ -80,7 +80,7 @@ enum {
        mode, reported separately and against the same n^2 pair count.  Same results within the same tolerances,
        still without atomics and bit-reproducible, but more workspace (one partial [T | D] per row for each of
        up to 64 groups of sample blocks: about 4.6 GiB at n = 2^20, d = 16).  Takes effect where it pays: for
-       sdkde_score at the samples themselves and sdkde_fit_eval with 6 <= d <= 32 and SDKDE_PREC_FP32; ignored
+       sdkde_score at the samples themselves and sdkde_fit_eval with 4 <= d <= 32 and SDKDE_PREC_FP32; ignored
        otherwise (sdkde_describe_plan tells). */
     SDKDE_FLAG_SYMMETRIC = 32
 };

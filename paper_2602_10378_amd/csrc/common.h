@@ -22,8 +22,7 @@ constexpr float kPadNorm = -1.0e30f;   // "-|x|^2" of a padding sample: exp2 of 
 constexpr float kPadCoord = 1.0e18f;   // thin-d padding coordinate: squared distance ~1e36, exp2(-that) = 0
 constexpr int kMeanBlocks = 128;
 constexpr int kFlushTiles = 64;         // sample tiles between folds of the running sums (power of two)
-constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3 in every input mode ...
-constexpr int kThinMaxDFp32 = 5;       // ... and up to d = 5 with fp32 inputs; MFMA path above
+constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3, MFMA path above
 
 // What a pair kernel accumulates.
 enum PairKind {

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
             const _Float16* ph = reinterpret_cast<const _Float16*>(ps) + i * 2 * dp + (c / 16) * 32 + (c % 16);
             pc = (float)ph[0] + (float)ph[16];
         } else {
-            pc = ps[i * dp + c];
+            pc = ps[i * dp + ((c & ~15) | ((c & 3) << 2) | ((c >> 2) & 3))];      // fp32 layout of the prepared rows
         }
     }
     float out = 0.0f;

@@ -18,9 +18,10 @@ namespace {
 // the B-operand layout (k = l/16, n = l%16) of the second MFMA for the four samples
 // j = 4*(l/16)+v, so Phi never leaves its registers: register v is the B operand of the MFMA
 // whose A operand holds samples {v, 4+v, 8+v, 12+v}; the blocked-transposed copy xt supplies
-// that A operand with one float4 load per lane.  The contraction order over coordinates in the
-// first MFMA is likewise permuted (MFMA kk contracts coordinates {kk, 4+kk, 8+kk, 12+kk} of each
-// 16-column block) so that both operands are plain float4 row loads.
+// that A operand with one float4 load per lane.  In the first contraction MFMA kk takes component kk of
+// every lane's float4, i.e. positions {kk, 4+kk, 8+kk, 12+kk} of each 16-column block, so that both
+// operands are plain float4 row loads; the fp32 prepared arrays place coordinate 4kk + g at position
+// 4g + kk, which makes those the coordinates 4kk .. 4kk+3 (see KLAST below).
 //
 // SELF (score at the samples themselves): the pair (i, i) must stay out of D and T, because
 // T_i/D_i - x_i would otherwise cancel against the large self term whenever a point has few
@@ -61,8 +62,13 @@ __device__ __forceinline__ f16x8 split_phi(const f32x4& phi)
 // bh[t][kb][1] = [lo | lo]; lane (r, g) holds elements 8g .. 8g+7 of that K axis, i.e. halves
 // 8(g&1) .. +7 of the hi (resp. lo) part.  Against the streamed A operand [hi | lo] the two MFMAs
 // sum hi*hi + lo*hi + hi*lo + lo*lo = the full product.
-template <int KB, int NI, int PREC>
+// KLAST (fp32 inputs only): MFMAs of the last 16-column block that contract real coordinates.  The prepared
+// fp32 arrays store coordinate c of a block at position 4 (c % 4) + c / 4, so that MFMA kk contracts
+// coordinates 4kk .. 4kk+3 and a block with d - 16 (KB - 1) <= 4 KLAST real coordinates needs only KLAST of
+// its four MFMAs (the skipped ones would multiply the zero padding).
+template <int KB, int NI, int PREC, int KLAST = 4>
 struct RowTiles {
+    static_assert(KLAST >= 1 && KLAST <= 4 && (KLAST == 4 || PREC == SDKDE_PREC_FP32), "partial last block: fp32 inputs only");
     f32x4 b[PREC == SDKDE_PREC_FP32 ? NI : 1][KB];
     f16x8 bh[PREC != SDKDE_PREC_FP32 ? NI : 1][KB][2];
     float ni[NI];
@@ -93,10 +99,11 @@ struct RowTiles {
     __device__ __forceinline__ f32x4 cross(int t, int kb, const f32x4& a, f32x4 c) const
     {
         if (PREC == SDKDE_PREC_FP32) {
+            const int steps = kb == KB - 1 ? KLAST : 4;      // compile-time after unrolling
             c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b[t][kb].x, c, 0, 0, 0);
-            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b[t][kb].y, c, 0, 0, 0);
-            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b[t][kb].z, c, 0, 0, 0);
-            c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b[t][kb].w, c, 0, 0, 0);
+            if (steps > 1) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b[t][kb].y, c, 0, 0, 0);
+            if (steps > 2) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b[t][kb].z, c, 0, 0, 0);
+            if (steps > 3) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b[t][kb].w, c, 0, 0, 0);
         } else {
             const f16x8 ah = __builtin_bit_cast(f16x8, a);
             c = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, bh[t][kb][0], c, 0, 0, 0);
@@ -134,7 +141,7 @@ __device__ __forceinline__ void store_partials(float* __restrict__ part_t, float
     }
 }
 
-template <int KB, int NI, int KIND, int PREC>
+template <int KB, int NI, int KIND, int PREC, int KLAST = 4>
 __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const float* __restrict__ ps, const float* __restrict__ pn, const float* __restrict__ xs,
     const float* __restrict__ xt, const float* __restrict__ xn, float* __restrict__ part_t,
@@ -157,7 +164,7 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
     const int64_t row_block = blockIdx.x / nsplit;
     const int64_t row0 = (row_block * kWavesPerBlock + wave) * (NI * kTile);
 
-    RowTiles<KB, NI, PREC> rows;
+    RowTiles<KB, NI, PREC, KLAST> rows;
     rows.load(ps, pn, row0, r, g);
     if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
         // every Phi of this kernel carries the factor 2^kPhiScaleLog2 (exact; removed from the sums at the end)

@@ -64,7 +64,8 @@ struct PrepJob {
 constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (two 16-sample tiles; 2 x 16.5 KiB of LDS)
 
 // Centre, scale and pad for the MFMA path.  A workgroup stages kPrepRows rows in LDS and writes
-//   dst[row][dp]   = a (x - mean), 0 in padding columns and rows (coalesced row writes),
+//   dst[row][dp]   = a (x - mean), 0 in padding columns and rows (coalesced row writes); fp32: within each
+//                    16-column block coordinate c sits at position 4 (c % 4) + c / 4,
 //   dst_t[row/16][col][row%16] = the same values with each 16-sample tile transposed (if dst_t),
 //   dst_n[row]     = -|dst[row]|^2 in double, rounded once; kPadNorm for padding rows.
 // prec >= SDKDE_PREC_FP16X2 (fp16x2 input modes): dst holds, per 16-column block, 16 fp16 "hi" values
@@ -103,7 +104,8 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
             out[16] = lo;
             v = (float)hi + (float)lo;
         } else {
-            job.dst[row * dp + c] = v;
+            // fp32 layout: coordinate c of a 16-column block at position 4 (c % 4) + c / 4 (RowTiles, KLAST)
+            job.dst[row * dp + ((c & ~15) | ((c & 3) << 2) | ((c >> 2) & 3))] = v;
         }
         used[rr][c] = v;
     }

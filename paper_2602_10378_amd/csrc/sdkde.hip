@@ -32,6 +32,13 @@ constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
     return second ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
 }
 
+// Whether pair_mfma_kernel is also built with fewer MFMAs for a partly filled last 16-column block (KLAST < 4):
+// fp32 inputs, d <= 32 (where the saving is largest: d = 6..8 needs 6 instead of 8 MFMAs per tile), main kinds.
+constexpr bool partial_last_block_built(int kb, int kind, int prec)
+{
+    return prec == SDKDE_PREC_FP32 && kb <= 2 && (kind == kScoreSelf || kind == kScorePoints || kind == kEval);
+}
+
 // Precision mode a call actually runs in: the thin path is fp32 VALU code; the fp16 second contraction is
 // built for dp <= 96 (beyond that its operands no longer fit the register file) and falls back to fp16x2.
 inline uint32_t effective_prec(uint32_t flags, bool thin, int dp)
@@ -62,6 +69,7 @@ struct Plan {
     int ntiles;           // 16-sample tiles
     int nsplit, tiles_per_split;
     int64_t row_blocks;
+    int klast;            // MFMAs of the last 16-column block that contract real coordinates: ceil((d - (dp - 16)) / 4)
     // symmetric mode of the score at the samples themselves (pair_sym_kernel), off unless sym_on
     bool sym_on;
     int sym_ni, sym_rb, sym_per_group, sym_nblocks, sym_ngroups;
@@ -81,11 +89,12 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
 {
     Plan p{};
     p.d = d;
-    // Direct differences on the VALU beat a zero-padded K = 16 contraction up to d = 5 with fp32 inputs (measured at
-    // n = 262144: score 25.5 / 29.2 ms at d = 4 / 5 against 36.3 ms, eval 4.6 / 5.2 against 5.5 ms; slower from
-    // d = 6 for eval, d = 7 for the score); with fp16 matrix inputs the matrix path wins from d = 4.
-    p.thin = d <= kThinMaxD || (d <= kThinMaxDFp32 && (flags & 15u) == SDKDE_PREC_FP32);
+    // Direct differences on the VALU up to d = 3.  (Measured at n = 262144, m = 65536, fp32: at d = 4 / 5 the VALU
+    // form takes 25.7 / 30.4 ms for the score and 4.7 / 5.5 ms for eval, the matrix path with the shortened last
+    // block 26.1 / 29.9 ms and 2.8 / 3.7 ms.)
+    p.thin = d <= kThinMaxD;
     p.dp = p.thin ? d : (int)round_up(d, 16);
+    p.klast = p.thin ? 4 : (d - (p.dp - 16) + 3) / 4;
     p.n_pad = round_up(n, kRowPad);
     p.m_pad = round_up(m > 0 ? m : 1, kRowPad);
     p.ntiles = (int)((n + 2 * kTile - 1) / (2 * kTile)) * 2;   // even: the pair kernel alternates two operand sets
@@ -253,11 +262,22 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
     // Host-side shape check: every row the grid touches exists in the padded arrays.
     if (p.row_blocks * p.rows_per_block > p.m_pad || (int64_t)p.ntiles * kTile > p.n_pad) return SDKDE_EINVAL;
 
+#define SDKDE_LAUNCH_MFMA_K(KB_, NI_, KLAST_)                                                                     \
+    hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, KIND, PREC, KLAST_>), grid, block, 0, st, w.ps, w.pn, w.xs,    \
+                       w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad,            \
+                       laplace_c0, shift)
 #define SDKDE_LAUNCH_MFMA(KB_, NI_)                                                                               \
     do {                                                                                                          \
-        hipLaunchKernelGGL((pair_mfma_kernel<KB_, NI_, KIND, PREC>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xt,  \
-                           w.xn, w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0,  \
-                           shift);                                                                                \
+        if constexpr (partial_last_block_built(KB_, KIND, PREC)) {                                                \
+            switch (p.klast) {                                                                                    \
+                case 1: SDKDE_LAUNCH_MFMA_K(KB_, NI_, 1); break;                                                  \
+                case 2: SDKDE_LAUNCH_MFMA_K(KB_, NI_, 2); break;                                                  \
+                case 3: SDKDE_LAUNCH_MFMA_K(KB_, NI_, 3); break;                                                  \
+                default: SDKDE_LAUNCH_MFMA_K(KB_, NI_, 4); break;                                                 \
+            }                                                                                                     \
+        } else {                                                                                                  \
+            SDKDE_LAUNCH_MFMA_K(KB_, NI_, 4);                                                                     \
+        }                                                                                                         \
         if constexpr (KIND == kScoreSelf || KIND == kScoreBand)                                                   \
             hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_, PREC>), dim3((unsigned)p.row_blocks), block, 0, st,   \
                                w.xs, w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                \
@@ -288,12 +308,6 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
             case 34: SDKDE_LAUNCH_THIN(3, 4); break;
             case 32: SDKDE_LAUNCH_THIN(3, 2); break;
             case 31: SDKDE_LAUNCH_THIN(3, 1); break;
-            case 44: SDKDE_LAUNCH_THIN(4, 4); break;
-            case 42: SDKDE_LAUNCH_THIN(4, 2); break;
-            case 41: SDKDE_LAUNCH_THIN(4, 1); break;
-            case 54: SDKDE_LAUNCH_THIN(5, 4); break;
-            case 52: SDKDE_LAUNCH_THIN(5, 2); break;
-            case 51: SDKDE_LAUNCH_THIN(5, 1); break;
             default: return SDKDE_EUNSUPPORTED;
         }
     } else {
@@ -329,6 +343,7 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
 #undef SDKDE_CASE_NI
 #undef SDKDE_LAUNCH_THIN
 #undef SDKDE_LAUNCH_MFMA
+#undef SDKDE_LAUNCH_MFMA_K
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 

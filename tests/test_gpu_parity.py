@@ -179,7 +179,7 @@ def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
 # work item, triangular items with more than one block) and the largest block size at small n.
 @pytest.mark.parametrize("n,d,seed,env", [
     (5000, 16, 0, {}), (5000, 16, 1, {"SDKDE_SYM_GROUPS": "3"}), (3000, 12, 2, {}), (7000, 20, 3, {}),
-    (6100, 32, 4, {"SDKDE_SYM_GROUPS": "4"}), (9000, 16, 5, {"SDKDE_SYM_RB": "2048"}), (4000, 6, 6, {"SDKDE_SYM_GROUPS": "1"}),
+    (6100, 32, 4, {"SDKDE_SYM_GROUPS": "4"}), (9000, 16, 5, {"SDKDE_SYM_RB": "2048"}), (4000, 5, 6, {"SDKDE_SYM_GROUPS": "1"}),
     (600, 16, 7, {}), (17, 8, 8, {}), (1, 16, 9, {})])
 def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
     P, torch = lib
@@ -213,7 +213,7 @@ def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
 def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib):
     P, torch = lib
     sym = P.SDKDE_FLAG_SYMMETRIC
-    for n, m, d, flags in ((3000, 500, 40, 0), (3000, 500, 16, P.SDKDE_PREC_FP16X2), (3000, 500, 2, 0), (3000, 500, 5, 0)):
+    for n, m, d, flags in ((3000, 500, 40, 0), (3000, 500, 16, P.SDKDE_PREC_FP16X2), (3000, 500, 2, 0)):
         print(f"symmetric flag ignored n={n} d={d} flags={flags}", flush=True)
         assert P.sdkde_describe_plan(n, n, d, 0, flags | sym)["symmetric"] == 0
         x, q, h = _mixture(n, m, d, 3)

@@ -15,7 +15,7 @@ FLAGS = [P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKD
 def _check(n, m, d, call, flags):
     p = P.sdkde_describe_plan(n, m, d, call, flags)
     rows = n if call == 0 else m
-    thin = d <= 3 or (d <= 5 and (flags & 15) == 0)
+    thin = d <= 3
     assert p["thin"] == int(thin)
     assert p["dp"] == (d if thin else -(-d // 16) * 16)
     # rows: the grid's row blocks cover all evaluation rows and stay inside the padded point array
@@ -56,7 +56,7 @@ def _check(n, m, d, call, flags):
 
 def _check_symmetric(p, n, d, call, flags):
     """The symmetric mode's decomposition: whole blocks, non-empty groups, LDS within the CU's 160 KiB."""
-    wanted = bool(flags & P.SDKDE_FLAG_SYMMETRIC) and call == 0 and 6 <= d <= 32 and (flags & 15) == 0
+    wanted = bool(flags & P.SDKDE_FLAG_SYMMETRIC) and call == 0 and 4 <= d <= 32 and (flags & 15) == 0
     assert p["symmetric"] == int(wanted)
     if not wanted:
         assert p["sym_block_rows"] == p["sym_blocks_per_group"] == p["sym_groups"] == 0
