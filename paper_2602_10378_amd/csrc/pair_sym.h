@@ -61,7 +61,7 @@ inline size_t sym_lds_bytes(int kb, int rb)
     return sizeof(float) * ((size_t)kb * rb * 16 + rb + kSymWaves * 16 * kTrStride);
 }
 
-template <int KB, int NI, int PREC>
+template <int KB, int NI, int PREC, int KLAST = 4>
 __global__ __launch_bounds__(kSymBlock) void pair_sym_kernel(
     const float* __restrict__ xs, const float* __restrict__ xt, const float* __restrict__ xn,
     float* __restrict__ part_t, float* __restrict__ part_d, int64_t n_pad, int rb, int nblocks, int per_group,
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kSymBlock) void pair_sym_kernel(
 
         for (int64_t a0 = a_lo; a0 < a_end; a0 += SB) {
             const int64_t row0 = a0 + (int64_t)wave * (NI * kTile);
-            RowTiles<KB, NI, PREC> rows;
+            RowTiles<KB, NI, PREC, KLAST> rows;      // KLAST: Gram MFMAs of a partly filled last block (pair_mfma.h)
             rows.load(xs, xn, row0, r, g);
             const float (&ni)[NI] = rows.ni;
             f32x4 xti[NI][KB];      // T_J contraction, A: coordinate 16mb + r of rows 4g .. 4g+3 of row tile t

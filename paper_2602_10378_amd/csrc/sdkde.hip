@@ -33,10 +33,11 @@ constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
 }
 
 // Whether pair_mfma_kernel is also built with fewer MFMAs for a partly filled last 16-column block (KLAST < 4):
-// fp32 inputs, d <= 32 (where the saving is largest: d = 6..8 needs 6 instead of 8 MFMAs per tile), main kinds.
+// fp32 inputs and d <= 32, where the saving is largest (d = 5..8 needs 6 instead of 8 MFMAs per tile in the score,
+// 2 instead of 4 in eval); every kind but the symmetric mode's in-block pass, which is a sliver of its work.
 constexpr bool partial_last_block_built(int kb, int kind, int prec)
 {
-    return prec == SDKDE_PREC_FP32 && kb <= 2 && (kind == kScoreSelf || kind == kScorePoints || kind == kEval);
+    return prec == SDKDE_PREC_FP32 && kb <= 2 && kind != kScoreBand;
 }
 
 // Precision mode a call actually runs in: the thin path is fp32 VALU code; the fp16 second contraction is
@@ -363,7 +364,7 @@ int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, const fl
 
 // Symmetric mode: pairs across blocks (pair_sym_kernel), then the pairs inside each block with the ordinary
 // kernels restricted to the block (slots ngroups + 1 and ngroups + 2).
-template <int KB, int NI, int PREC>
+template <int KB, int NI, int PREC, int KLAST>
 int launch_sym_kernel(const Plan& p, const Workspace& w, hipStream_t st)
 {
     const size_t lds = sym_lds_bytes(KB, p.sym_rb);
@@ -374,12 +375,12 @@ int launch_sym_kernel(const Plan& p, const Workspace& w, hipStream_t st)
     int dev = 0;
     SDKDE_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= kMaxDevices || lds > lds_allowed[dev]) {
-        SDKDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&pair_sym_kernel<KB, NI, PREC>),
+        SDKDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&pair_sym_kernel<KB, NI, PREC, KLAST>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         if (dev >= 0 && dev < kMaxDevices) lds_allowed[dev] = lds;
     }
     const int64_t items = (int64_t)p.sym_ngroups * (p.sym_ngroups + 1) / 2;
-    hipLaunchKernelGGL((pair_sym_kernel<KB, NI, PREC>), dim3((unsigned)items), dim3(kSymBlock), lds, st, w.xs, w.xt,
+    hipLaunchKernelGGL((pair_sym_kernel<KB, NI, PREC, KLAST>), dim3((unsigned)items), dim3(kSymBlock), lds, st, w.xs, w.xt,
                        w.xn, w.part_t, w.part_d, p.n_pad, p.sym_rb, p.sym_nblocks, p.sym_per_group, p.sym_ngroups);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
@@ -390,7 +391,12 @@ int launch_sym_kb(const Plan& p, const Workspace& w, hipStream_t st)
     constexpr int NI = sym_row_tiles(KB, PREC);
     if constexpr (NI > 0) {
         if (p.sym_ni != NI) return SDKDE_EINVAL;
-        return launch_sym_kernel<KB, NI, PREC>(p, w, st);
+        switch (p.klast) {
+            case 1: return launch_sym_kernel<KB, NI, PREC, 1>(p, w, st);
+            case 2: return launch_sym_kernel<KB, NI, PREC, 2>(p, w, st);
+            case 3: return launch_sym_kernel<KB, NI, PREC, 3>(p, w, st);
+            default: return launch_sym_kernel<KB, NI, PREC, 4>(p, w, st);
+        }
     } else {
         return SDKDE_EUNSUPPORTED;
     }
