@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes per launch of the score main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
 # read counter x2 and write counter x1 after calibration on the debias kernel): profiles/pipeline_<config>_*.txt
-SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4586061.6 * 2 + 557056.0) * 1024, "C4": (2371088.4 * 2 + 532480.0) * 1024}
+SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4585940.9 * 2 + 557056.0) * 1024, "C4": (2370965.2 * 2 + 532480.0) * 1024}
 PAPER_PAIRS_PER_S_C5 = (1048576.0**2 + 131072.0 * 1048576.0) / 2.3   # paper: 2.3 s on one RTX A6000 (TF32)
 
 
