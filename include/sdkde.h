@@ -168,6 +168,8 @@ int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, in
  *   [18] partial slots       [19] size factor of the transposed copy (2 in the FP16X2_ALL mode)
  * and, when out_len >= 24: [20] symmetric mode in effect   [21] rows per sample block   [22] blocks per group
  *   [23] groups (work items = groups (groups + 1) / 2)
+ * and, when out_len >= 25: [24] matrix instructions of the first contraction spent on the last 16-column block
+ *   (4 = all; fewer when the block holds at most 12 real coordinates: fp32 inputs, d <= 32)
  */
 int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t flags, int64_t *out,
                         int32_t out_len);

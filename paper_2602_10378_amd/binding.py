@@ -89,7 +89,7 @@ def sdkde_workspace_bytes(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) 
 PLAN_FIELDS = ("thin", "dp", "row_tiles", "rows_per_block", "row_blocks", "splits", "tiles_per_split", "tiles",
                "n_pad", "m_pad", "workspace_bytes", "off_xs", "off_xt", "off_xn", "off_ps", "off_pn", "off_part_t",
                "off_part_d", "partial_slots", "xt_scale", "symmetric", "sym_block_rows", "sym_blocks_per_group",
-               "sym_groups")
+               "sym_groups", "last_block_mfmas")
 
 
 def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PREC_FP32) -> dict:

@@ -675,6 +675,9 @@ int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t 
         out[22] = p.sym_on ? p.sym_per_group : 0;
         out[23] = p.sym_on ? p.sym_ngroups : 0;
     }
+    if (out_len >= 25)
+        out[24] = (!p.thin && partial_last_block_built(p.dp / 16, score ? kScoreSelf : kEval, (int)effective_prec(flags, p.thin, p.dp)))
+                      ? p.klast : 4;
     return SDKDE_OK;
 }
 

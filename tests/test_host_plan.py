@@ -51,6 +51,11 @@ def _check(n, m, d, call, flags):
         assert off + size <= nxt[1], f"{name} overlaps {nxt[0]}"
     assert p["workspace_bytes"] <= P.sdkde_workspace_bytes(n, m if call else max(m, 1), d, flags)
     _check_symmetric(p, n, d, call, flags)
+    # first-contraction MFMAs of the last 16-column block: only the real coordinates (fp32 inputs, d <= 32)
+    if not thin and (flags & 15) == 0 and d <= 32:
+        assert p["last_block_mfmas"] == -(-(d - (p["dp"] - 16)) // 4)
+    else:
+        assert p["last_block_mfmas"] == 4
     return p
 
 
