@@ -80,8 +80,8 @@ enum {
        mode, reported separately and against the same n^2 pair count.  Same results within the same tolerances,
        still without atomics and bit-reproducible, but more workspace (one partial [T | D] per row for each of
        up to 64 groups of sample blocks: about 4.6 GiB at n = 2^20, d = 16).  Takes effect where it pays: for
-       sdkde_score at the samples themselves and sdkde_fit_eval with 4 <= d <= 32 and SDKDE_PREC_FP32; ignored
-       otherwise (sdkde_describe_plan tells). */
+       sdkde_score at the samples themselves and sdkde_fit_eval with 4 <= d <= 32, SDKDE_PREC_FP32 and enough samples to fill the chip with its work
+       items (n >= 32768 at d <= 16, n >= 16384 at d <= 32); ignored otherwise (sdkde_describe_plan tells). */
     SDKDE_FLAG_SYMMETRIC = 32
 };
 

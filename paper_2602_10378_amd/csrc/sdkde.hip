@@ -188,11 +188,19 @@ void apply_symmetric(Plan& p, int64_t n, uint32_t flags, bool self)
     const int64_t n_pad = round_up(n, rb > kRowPad ? rb : kRowPad);
     const int64_t nblocks = n_pad / rb;
     if (nblocks > (1 << 20)) return;
+    const int per_group = (int)((nblocks + max_groups - 1) / max_groups);
+    const int ngroups = (int)((nblocks + per_group - 1) / per_group);
+    // Below ~512 work items (two rounds of one per CU) the ordinary kernels win: measured at d = 16 the mode pays
+    // from n = 32768 (528 items) and loses 1.5x at n = 24576 (300 items), 4x at n = 8192; at d = 32 it pays from
+    // n = 16384.  The flag is then ignored.  (SDKDE_SYM_MIN_ITEMS: for tests of the mode at small sizes.)
+    int min_items = env_int("SDKDE_SYM_MIN_ITEMS", 512);
+    if (min_items < 1) min_items = 1;
+    if ((int64_t)ngroups * (ngroups + 1) / 2 < min_items) return;
     p.sym_on = true;
     p.sym_rb = rb;
     p.sym_nblocks = (int)nblocks;
-    p.sym_per_group = (int)((nblocks + max_groups - 1) / max_groups);
-    p.sym_ngroups = (int)((nblocks + p.sym_per_group - 1) / p.sym_per_group);
+    p.sym_per_group = per_group;
+    p.sym_ngroups = ngroups;
     p.n_pad = p.m_pad = n_pad;          // whole blocks; the points are the samples
 }
 

@@ -187,6 +187,7 @@ def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
         monkeypatch.delenv(key, raising=False)
     for key, value in env.items():
         monkeypatch.setenv(key, value)
+    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")      # the mode is otherwise declined below ~512 work items
     flags = P.SDKDE_FLAG_SYMMETRIC
     plan = P.sdkde_describe_plan(n, n, d, 0, flags)
     print(f"symmetric n={n} d={d} env={env} block={plan['sym_block_rows']} per_group={plan['sym_blocks_per_group']} "
@@ -210,9 +211,14 @@ def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
     print(f"symmetric n={n} d={d}: worst {worst:.3g} of allowance, rel frobenius {frob:.3g}", flush=True)
 
 
-def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib):
+def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib, monkeypatch):
     P, torch = lib
     sym = P.SDKDE_FLAG_SYMMETRIC
+    # too few samples to fill the chip with its work items: declined
+    monkeypatch.delenv("SDKDE_SYM_MIN_ITEMS", raising=False)
+    assert P.sdkde_describe_plan(8192, 8192, 16, 0, sym)["symmetric"] == 0
+    assert P.sdkde_describe_plan(32768, 32768, 16, 0, sym)["symmetric"] == 1
+    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")
     for n, m, d, flags in ((3000, 500, 40, 0), (3000, 500, 16, P.SDKDE_PREC_FP16X2), (3000, 500, 2, 0)):
         print(f"symmetric flag ignored n={n} d={d} flags={flags}", flush=True)
         assert P.sdkde_describe_plan(n, n, d, 0, flags | sym)["symmetric"] == 0

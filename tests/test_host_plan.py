@@ -62,7 +62,11 @@ def _check(n, m, d, call, flags):
 def _check_symmetric(p, n, d, call, flags):
     """The symmetric mode's decomposition: whole blocks, non-empty groups, LDS within the CU's 160 KiB."""
     wanted = bool(flags & P.SDKDE_FLAG_SYMMETRIC) and call == 0 and 4 <= d <= 32 and (flags & 15) == 0
-    assert p["symmetric"] == int(wanted)
+    if not wanted:
+        assert p["symmetric"] == 0
+    elif p["symmetric"] == 0:        # declined: too few work items to fill the chip
+        assert n < 32768 * 2048 // 1024
+    wanted = bool(p["symmetric"])
     if not wanted:
         assert p["sym_block_rows"] == p["sym_blocks_per_group"] == p["sym_groups"] == 0
         return
@@ -74,6 +78,7 @@ def _check_symmetric(p, n, d, call, flags):
     assert 1 <= groups <= 64 and per_group >= 1
     assert groups * per_group >= blocks > (groups - 1) * per_group
     assert p["partial_slots"] == groups + 3
+    assert groups * (groups + 1) // 2 >= 512
     assert 4 * ((p["dp"] // 16) * rb * 16 + rb + 8 * 16 * 20) <= 160 * 1024
 
 
