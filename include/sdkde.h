@@ -82,7 +82,15 @@ enum {
        up to 64 groups of sample blocks: about 4.6 GiB at n = 2^20, d = 16).  Takes effect where it pays: for
        sdkde_score at the samples themselves and sdkde_fit_eval with 4 <= d <= 32, SDKDE_PREC_FP32 and enough samples to fill the chip with its work
        items (n >= 32768 at d <= 16, n >= 16384 at d <= 32); ignored otherwise (sdkde_describe_plan tells). */
-    SDKDE_FLAG_SYMMETRIC = 32
+    SDKDE_FLAG_SYMMETRIC = 32,
+    /* flags bit 6, sdkde_eval and sdkde_eval_laplace only (evaluating one fitted estimate at many batches of
+       queries): the workspace still holds what the previous sdkde_eval / sdkde_eval_laplace call on it prepared
+       from the same samples, n, d, h and precision mode, and nothing else has used the workspace since: the
+       column means and the prepared samples are reused and only the queries are prepared (m may differ from
+       call to call; at n = 2^20 this saves about 0.3 ms per call).  The samples pointer is not read.  With
+       contents from anything else the results are wrong without notice.  Other calls return
+       SDKDE_EUNSUPPORTED for it. */
+    SDKDE_FLAG_SAMPLES_PREPARED = 64
 };
 
 /*

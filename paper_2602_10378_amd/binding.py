@@ -19,6 +19,7 @@ SDKDE_PREC_FP16X2 = 1
 SDKDE_PREC_FP16X2_ALL = 2
 SDKDE_FLAG_MAX_SHIFT = 16
 SDKDE_FLAG_SYMMETRIC = 32
+SDKDE_FLAG_SAMPLES_PREPARED = 64
 SDKDE_MAX_D = 128
 
 _lib = None
@@ -109,6 +110,8 @@ def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PRE
 
 def _workspace(ws, n, m, d, device, flags=SDKDE_PREC_FP32):
     if ws is None:
+        if flags & SDKDE_FLAG_SAMPLES_PREPARED:
+            raise ValueError("SDKDE_FLAG_SAMPLES_PREPARED needs the workspace of the call that prepared the samples")
         ws = make_workspace(n, m, d, device, flags)
     if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
         raise TypeError("workspace must be a contiguous uint8 tensor on the GPU")

@@ -8,6 +8,42 @@ namespace {
 // Split reduction + epilogues (fixed summation order over splits: deterministic).
 // ------------------------------------------------------------------------------------------
 
+// The partial slots of one output are shared by PARTS threads (slots part, part + PARTS, ...), which keeps many
+// loads in flight instead of one long dependent chain on a few compute units (a call with few points has up to
+// thousands of slots and few outputs), and are combined through LDS in the fixed order part 0, 1, ..., PARTS - 1.
+// The host picks PARTS from the slot and output counts alone (epilogue_parts), so a plan always sums in the same
+// order: the many-thread form only where the outputs are too few to fill the chip otherwise, since its loads are
+// narrow (kBlock / PARTS consecutive floats per slot).
+constexpr int kEpiPartsFew = 4, kEpiPartsMany = 32;
+constexpr int kEpiManySlots = 64;                   // least slot count and
+constexpr int64_t kEpiFewOutputs = 65536;           // most outputs for kEpiPartsMany
+inline int epilogue_parts(int nslots, int64_t outputs)
+{
+    return nslots >= kEpiManySlots && outputs <= kEpiFewOutputs ? kEpiPartsMany : kEpiPartsFew;
+}
+
+template <int PARTS, bool MAX>
+__device__ __forceinline__ float reduce_slots(const float* __restrict__ first, int64_t stride, int nslots, bool active,
+                                              float (*red)[kBlock / PARTS])
+{
+    constexpr int OUTPUTS = kBlock / PARTS;
+    const int lane = threadIdx.x % OUTPUTS, part = threadIdx.x / OUTPUTS;
+    float acc = MAX ? kNegHuge : 0.0f;
+    if (active) {
+        for (int s = part; s < nslots; s += PARTS) {
+            const float v = first[(int64_t)s * stride];
+            acc = MAX ? fmaxf(acc, v) : acc + v;
+        }
+    }
+    red[part][lane] = acc;
+    __syncthreads();
+    float r = red[0][lane];
+#pragma unroll
+    for (int q = 1; q < PARTS; ++q) r = MAX ? fmaxf(r, red[q][lane]) : r + red[q][lane];
+    __syncthreads();            // red is reused by the next reduction
+    return r;
+}
+
 // ps_split_half: p~ is stored as fp16 hi/lo pairs (fp16x2 input mode) and is rebuilt as hi + lo.
 // mode 0 (MFMA path, separate points): score = (T/D - p~) * inv_ah2            (T = Phi X regrouping)
 // mode 1 (thin path):                   score = (N/D) * inv_ah2                (direct-form numerator)
@@ -15,20 +51,22 @@ namespace {
 //        where T', D' exclude the pair (i, i), whose weight is exactly 1.
 // inv_ah2 = 1 / (a h^2) undoes the coordinate scaling.  D == 0 gives 0.
 // score and x_sd are both optional outputs; x_sd = x + half_h2 * score (x: the original points, same indexing).
+// Grid: one workgroup per kBlock / PARTS elements of the [m, d] output.
+template <int PARTS>
 __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
     const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
     int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, int ps_split_half, float inv_ah2,
     float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd)
 {
-    int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (idx >= m * d) return;
-    const int64_t i = idx / d;
-    const int c = (int)(idx % d);
-    float tsum = 0.0f, dsum = 0.0f;
-    for (int s = 0; s < nsplit; ++s) {
-        tsum += part_t[((int64_t)s * m_pad + i) * dp + c];
-        dsum += part_d[(int64_t)s * m_pad + i];
-    }
+    constexpr int kEpiOutputs = kBlock / PARTS;
+    __shared__ float red[PARTS][kEpiOutputs];
+    const int64_t idx = (int64_t)blockIdx.x * kEpiOutputs + threadIdx.x % kEpiOutputs;
+    const bool active = idx < m * d;
+    const int64_t i = active ? idx / d : 0;
+    const int c = active ? (int)(idx % d) : 0;
+    const float tsum = reduce_slots<PARTS, false>(part_t + i * dp + c, m_pad * dp, nsplit, active, red);
+    const float dsum = reduce_slots<PARTS, false>(part_d + i, m_pad, nsplit, active, red);
+    if (!active || threadIdx.x >= kEpiOutputs) return;
     float pc = 0.0f;                       // p~_i[c]
     if (mode != 1) {
         if (ps_split_half) {
@@ -52,16 +90,20 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
 // log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
 // signed != 0 (Laplace-corrected sum, which may be negative): density = sum * exp(lognorm) only.
 // shift (may be null): per-query base-2 exponent shift of the max-shifted mode.
+// Grid: one workgroup per kBlock / PARTS queries.
+template <int PARTS>
 __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __restrict__ part_d, int nsplit,
                                                                int64_t m, int64_t m_pad, double lognorm, int is_signed,
                                                                const float* __restrict__ shift,
                                                                float* __restrict__ density,
                                                                float* __restrict__ log_density)
 {
-    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i >= m) return;
-    float dsum = 0.0f;
-    for (int s = 0; s < nsplit; ++s) dsum += part_d[(int64_t)s * m_pad + i];
+    constexpr int kEpiOutputs = kBlock / PARTS;
+    __shared__ float red[PARTS][kEpiOutputs];
+    const int64_t i = (int64_t)blockIdx.x * kEpiOutputs + threadIdx.x % kEpiOutputs;
+    const bool active = i < m;
+    const float dsum = reduce_slots<PARTS, false>(part_d + (active ? i : 0), m_pad, nsplit, active, red);
+    if (!active || threadIdx.x >= kEpiOutputs) return;
     // max-shifted mode: the sums were taken of phi / 2^shift
     const double shift_ln = shift ? (double)shift[i] * 0.69314718055994530942 : 0.0;
     if (is_signed) {
@@ -83,13 +125,17 @@ __global__ __launch_bounds__(kBlock) void debias_kernel(const float* __restrict_
 
 // shift[i] = max over splits of the row maxima left in part_d by a kRowMax pass; on the MFMA path the
 // shift is also folded into the row constant pn (-|p~|^2 - shift), so the main pass needs no extra work.
+// Grid: one workgroup per kBlock / PARTS rows.
+template <int PARTS>
 __global__ __launch_bounds__(kBlock) void shift_kernel(const float* __restrict__ part_d, int nsplit, int64_t m_pad,
                                                        float* __restrict__ shift, float* __restrict__ pn)
 {
-    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i >= m_pad) return;
-    float mx = kNegHuge;
-    for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, part_d[(int64_t)s * m_pad + i]);
+    constexpr int kEpiOutputs = kBlock / PARTS;
+    __shared__ float red[PARTS][kEpiOutputs];
+    const int64_t i = (int64_t)blockIdx.x * kEpiOutputs + threadIdx.x % kEpiOutputs;
+    const bool active = i < m_pad;
+    const float mx = reduce_slots<PARTS, true>(part_d + (active ? i : 0), m_pad, nsplit, active, red);
+    if (!active || threadIdx.x >= kEpiOutputs) return;
     shift[i] = mx;
     if (pn) pn[i] -= mx;
 }

@@ -439,13 +439,27 @@ int launch_symmetric(const Plan& p, const Workspace& w, uint32_t flags, hipStrea
     return launch_pair_prec<kScoreBand>(band, wb, flags, nullptr, st);
 }
 
+// Launches an epilogue kernel (template parameter: threads per output) over `outputs` outputs of `nslots` slots.
+#define SDKDE_LAUNCH_EPILOGUE(KERNEL, nslots, outputs, st, ...)                                                    \
+    do {                                                                                                           \
+        if (epilogue_parts(nslots, outputs) == kEpiPartsMany) {                                                    \
+            constexpr int per_wg = kBlock / kEpiPartsMany;                                                         \
+            hipLaunchKernelGGL(KERNEL<kEpiPartsMany>, dim3((unsigned)(((outputs) + per_wg - 1) / per_wg)),         \
+                               dim3(kBlock), 0, st, __VA_ARGS__);                                                  \
+        } else {                                                                                                   \
+            constexpr int per_wg = kBlock / kEpiPartsFew;                                                          \
+            hipLaunchKernelGGL(KERNEL<kEpiPartsFew>, dim3((unsigned)(((outputs) + per_wg - 1) / per_wg)),          \
+                               dim3(kBlock), 0, st, __VA_ARGS__);                                                  \
+        }                                                                                                          \
+    } while (0)
+
 // First pass of the max-shifted mode for separate points: row maxima of the exponent, then shift_kernel.
 int launch_max_shift(const Plan& p, const Workspace& w, uint32_t flags, hipStream_t st)
 {
     int rc = launch_pair_prec<kRowMax>(p, w, flags, nullptr, st);
     if (rc != SDKDE_OK) return rc;
-    hipLaunchKernelGGL(shift_kernel, dim3((unsigned)((p.m_pad + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
-                       p.nsplit, p.m_pad, w.shift, p.thin ? nullptr : w.pn);
+    SDKDE_LAUNCH_EPILOGUE(shift_kernel, p.nsplit, p.m_pad, st, w.part_d, p.nsplit, p.m_pad, w.shift,
+                          p.thin ? nullptr : w.pn);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
@@ -479,7 +493,7 @@ int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int6
 int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h, uint32_t flags)
 {
     if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
-    if (d > SDKDE_MAX_D || (flags & ~(15u | SDKDE_FLAG_MAX_SHIFT | SDKDE_FLAG_SYMMETRIC)) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_ALL)
+    if (d > SDKDE_MAX_D || (flags & ~(15u | SDKDE_FLAG_MAX_SHIFT | SDKDE_FLAG_SYMMETRIC | SDKDE_FLAG_SAMPLES_PREPARED)) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_ALL)
         return SDKDE_EUNSUPPORTED;
     if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
     return SDKDE_OK;
@@ -510,6 +524,7 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     if (!score_out && !samples_sd_out) return SDKDE_EINVAL;
     if (samples_sd_out && !self) return SDKDE_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+    if (flags & SDKDE_FLAG_SAMPLES_PREPARED) return SDKDE_EUNSUPPORTED;      // sdkde_eval / sdkde_eval_laplace only
     flags = anchored_flags(flags, self);
 
     Plan p = make_plan(n, m, d, true, flags);
@@ -539,11 +554,10 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
 
     const int64_t total = m * (int64_t)d;
     const float inv_ah2 = (float)(1.0 / (a * h * h));
-    hipLaunchKernelGGL(score_epilogue_kernel, dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
-                       w.part_t, w.part_d, w.ps, p.sym_on ? p.sym_ngroups + 3 : p.nsplit + ((self && !p.thin) ? 1 : 0), m,
-                       p.m_pad, d, p.dp,
-                       p.thin ? 1 : (self ? 2 : 0), effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0, inv_ah2,
-                       score_out, samples, (float)(0.5 * h * h), samples_sd_out);
+    const int nslots = p.sym_on ? p.sym_ngroups + 3 : p.nsplit + ((self && !p.thin) ? 1 : 0);
+    SDKDE_LAUNCH_EPILOGUE(score_epilogue_kernel, nslots, total, st, w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp,
+                          p.thin ? 1 : (self ? 2 : 0), effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0,
+                          inv_ah2, score_out, samples, (float)(0.5 * h * h), samples_sd_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
@@ -565,10 +579,16 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
 
     const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
     // reuse_mean: w.mean_partial still holds the column sums of an earlier pass over (nearly) the same points
-    if (!reuse_mean && (rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
     const PrepJob sample_job{samples, n, p.n_pad, w.xs, nullptr, w.xn, kPadCoord};
     const PrepJob query_job{queries, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
-    if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+    if (flags & SDKDE_FLAG_SAMPLES_PREPARED) {
+        // the workspace still holds the column sums and the prepared samples (their place in the workspace depends
+        // on n, d and the precision mode only, not on m): only the queries are prepared
+        if ((rc = launch_prep(p, query_job, PrepJob{}, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+    } else {
+        if (!reuse_mean && (rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
+        if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+    }
 
     if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
     const bool shifted = (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
@@ -579,8 +599,8 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
 
     const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
-    hipLaunchKernelGGL(eval_epilogue_kernel, dim3((unsigned)((m + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, w.part_d,
-                       p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0, shift, density_out, log_density_out);
+    SDKDE_LAUNCH_EPILOGUE(eval_epilogue_kernel, p.nsplit, m, st, w.part_d, p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0,
+                          shift, density_out, log_density_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 

@@ -174,6 +174,36 @@ def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
     assert worst_s <= 1.0
 
 
+# Evaluating one fitted estimate at batch after batch of queries: with SDKDE_FLAG_SAMPLES_PREPARED the samples
+# prepared by the previous eval call on the same workspace are reused; the results must be the bits of a fresh call.
+@pytest.mark.parametrize("n,d,flags", [(5000, 16, 0), (3000, 2, 0), (4000, 7, 0), (2500, 20, 1), (3000, 16, 16), (2000, 40, 17)])
+def test_eval_with_samples_prepared_by_the_previous_call(lib, n, d, flags):
+    P, torch = lib
+    print(f"samples prepared n={n} d={d} flags={flags}", flush=True)
+    x, q, h = _mixture(n, 1500, d, 12)
+    xd = torch.from_numpy(x).cuda()
+    batches = [torch.from_numpy(np.ascontiguousarray(q[a:b])).cuda() for a, b in ((0, 700), (700, 701), (701, 1500))]
+    m_max = max(b.shape[0] for b in batches)
+    ws = P.make_workspace(n, m_max, d, flags=flags)
+    prepared = flags | P.SDKDE_FLAG_SAMPLES_PREPARED
+    first = P.sdkde_eval(xd, batches[0], h, want="both", workspace=ws, flags=flags)
+    for k, qb in enumerate(batches[1:]):
+        got = P.sdkde_eval(xd, qb, h, want="both", workspace=ws, flags=prepared)
+        lap = P.sdkde_eval_laplace(xd, qb, h, workspace=ws, flags=prepared)
+        fresh_ws = P.make_workspace(n, m_max, d, flags=flags)
+        want = P.sdkde_eval(xd, qb, h, want="both", workspace=fresh_ws, flags=flags)
+        want_lap = P.sdkde_eval_laplace(xd, qb, h, workspace=fresh_ws, flags=flags)
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1]), f"batch {k + 1}"
+        assert torch.equal(lap, want_lap), f"batch {k + 1} (Laplace)"
+    assert_log_density_close(first[1].cpu().numpy(), oracle.eval_log_density(x, q[:700], h), "first batch")
+    # the score calls do not take the flag, and the binding refuses to invent a workspace for it
+    with pytest.raises(P.SdkdeError) as e:
+        P.sdkde_score(xd, h, workspace=ws, flags=prepared)
+    assert e.value.status == 2
+    with pytest.raises(ValueError):
+        P.sdkde_eval(xd, batches[0], h, flags=prepared)
+
+
 # Symmetric score (separate mode): every unordered pair of samples computed once.  Sizes span several sample
 # blocks and groups of blocks with ragged tails; the environment overrides force few groups (several blocks per
 # work item, triangular items with more than one block) and the largest block size at small n.

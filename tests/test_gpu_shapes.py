@@ -140,14 +140,22 @@ def test_profile_instrumentation_counts_launches_on_the_callers_stream():
     ws = P.make_workspace(20000, 3000, 16)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
-    P.sdkde_score(xd, h, workspace=ws)                 # warm-up, not recorded
-    torch.cuda.synchronize()
+    # Outputs allocated beforehand and three untimed calls on the side stream with recording on (which creates
+    # the record's events), so that the timed region below holds launches only: the stream events also see
+    # any gap the host leaves between launches.
+    score = torch.empty_like(xd)
     P.sdkde_profile_enable(True)
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            P.sdkde_score(xd, h, out=score, workspace=ws)
+    torch.cuda.synchronize()
+    P.sdkde_profile_enable(False)
+    P.sdkde_profile_enable(True)                       # starts an empty record
     t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     with torch.cuda.stream(side):
         t0.record()
         for _ in range(3):
-            P.sdkde_score(xd, h, workspace=ws)
+            P.sdkde_score(xd, h, out=score, workspace=ws)
         t1.record()
         P.sdkde_eval(xd, qd, h, workspace=ws)
     torch.cuda.synchronize()
