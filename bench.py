@@ -19,7 +19,9 @@ PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes per launch of the score main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
 # read counter x2 and write counter x1 after calibration on the debias kernel): profiles/pipeline_<config>_*.txt
 SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4585940.9 * 2 + 557056.0) * 1024, "C4": (2370965.2 * 2 + 532480.0) * 1024}
-PAPER_PAIRS_PER_S_C5 = (1048576.0**2 + 131072.0 * 1048576.0) / 2.3   # paper: 2.3 s on one RTX A6000 (TF32)
+# The paper's two timed shapes (one RTX A6000, TF32 dots), keyed by (config, n, m): seconds end to end.
+PAPER_SECONDS = {("C5", 1048576, 131072): 2.3,        # abstract / conclusion
+                 ("C2", 32768, 4096): 2.11e-3}        # runtime table of the Results section (run with --config C2 --m 4096)
 
 
 def cpu_baseline(x, q, h, budget_s=15.0):
@@ -144,6 +146,7 @@ def main():
         s.copy_(s_fp32)
 
     pairs = float(n) * n + float(m) * n
+    paper_s = PAPER_SECONDS.get((args.config, n, m))
     ms_per_step = dt / args.steps * 1e3
     value = pairs / (dt / args.steps)
     score_avg_ms = score_ms / max(score_launches, 1)
@@ -155,8 +158,9 @@ def main():
         "metric": "pair-interactions/sec (score n^2 + eval m*n)", "value": value, "unit": "pairs/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": (value / PAPER_PAIRS_PER_S_C5) if (args.config == "C5" and args.n is None and args.m is None) else None,
-        "baseline_note": "paper: 2.3 s end-to-end at this shape on one RTX A6000 with TF32 dots (context, other hardware)",
+        "vs_baseline": (paper_s / (dt / args.steps)) if paper_s else None,
+        "baseline_note": (f"paper: {paper_s:g} s end-to-end at this shape on one RTX A6000 with TF32 dots "
+                          "(context, other hardware)") if paper_s else None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n} samples, m={m} queries, d={d}, Gaussian mixture, "
                                f"Silverman h={h:.4f}, score+debias+eval", "n": n, "m": m, "d": d, "seed": args.seed},

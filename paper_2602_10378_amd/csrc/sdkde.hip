@@ -83,8 +83,54 @@ int env_int(const char* name, int fallback)
     return atoi(v);
 }
 
-// Workgroups needed to keep 256 CUs busy with a few waves per SIMD.
+// Workgroups needed to keep 256 CUs busy with a few waves per SIMD (thin path and tiny problems).
 constexpr int64_t kTargetBlocks = 2048;
+constexpr int kComputeUnits = 256;
+
+// Relative cost per unit of work of running the matrix-path kernels with `ni` row tiles per wave instead of the
+// best count (operand reuse against register pressure), measured on MI355X at n = 65536 .. 262144 with fp32
+// inputs: score d = 16: 2 / 4 / 8 row tiles 2.67 / 2.37 / 2.37 ms (n = 65536); d = 64: 2 / 4: 9.67 / 8.11 ms;
+// eval d = 16 (n = 262144, m = 65536): 2 / 4 / 8 / 16: 5.70 / 5.55 / 5.51 / 5.57 ms; d = 32: 2 / 4 / 8:
+// 9.57 / 9.21 / 9.10 ms; d = 64: 2 / 4: 20.8 / 17.6 ms.
+double row_tiles_penalty(bool score, int kb, int ni)
+{
+    if (kb >= 5) return 1.0;                                  // only ni = 2 is built
+    if (score) return ni >= 8 ? 1.0 : ni == 4 ? (kb == 1 ? 1.004 : 1.0) : (kb == 1 ? 1.12 : 1.15);
+    if (kb == 1) return ni == 16 ? 1.013 : ni == 8 ? 1.0 : ni == 4 ? 1.005 : 1.035;
+    if (kb == 2) return ni == 8 ? 1.0 : ni == 4 ? 1.008 : 1.05;
+    return ni == 4 ? 1.0 : 1.17;
+}
+
+// Estimated time of the pair kernel plus its share of the epilogue for `ni` row tiles per wave and `nsplit`
+// splits, in units of one wave's time for one 16 x 16 tile.  A compute unit works through its
+// ceil(workgroups / 256) workgroups at a rate that does not depend on how many are resident (the kernels are
+// bound by instruction issue), so the time is rounds x (work of a workgroup), plus a tail that grows with the
+// length of a workgroup, plus the traffic of one more partial slot per split (written once, read once, at about
+// 3 TB/s).  Fitted to sweeps over (ni, nsplit) at d = 16 .. 128, n = 8192 .. 1048576, m = 1024 .. 200000: the
+// pick is within 0.3 % of the best measured pair on average (2.3 % at worst), where "as many workgroups as
+// fill the chip eight times" was 4.7 % off on average and up to 28 % at n = 8192 .. 24576.
+double plan_cost(bool score, int kb, uint32_t prec, int64_t m, int64_t m_pad, int ntiles, int ni, int nsplit)
+{
+    const int64_t row_blocks = (m + kWavesPerBlock * kTile * ni - 1) / (kWavesPerBlock * kTile * ni);
+    const int64_t groups = row_blocks * nsplit;
+    const int64_t rounds = (groups + kComputeUnits - 1) / kComputeUnits;
+    int tps = (ntiles + nsplit - 1) / nsplit;
+    tps += tps & 1;
+    double work = (double)rounds * ni * (tps + 1.0) * row_tiles_penalty(score, kb, ni);
+    // two row tiles per wave at d >= 49 re-read the sample tiles from L2 four times per workgroup: a lone
+    // workgroup per compute unit keeps them in the vector cache (measured 0.36 against 0.43 ms at d = 128,
+    // n = 32768, m = 4096)
+    if (ni == 2 && kb >= 4 && groups <= kComputeUnits) work *= 0.85;
+    const double tail = 0.1 * ni * tps;
+    // clocks per tile: the MFMAs at their measured issue time (33 clocks in fp32; the fp16 modes in proportion to
+    // their measured kernel times), plus exp and sums
+    double tile_clk = 33.0 * (score ? 8 : 4) * kb + 50.0;
+    if (prec == SDKDE_PREC_FP16X2) tile_clk *= 0.62;
+    if (prec == SDKDE_PREC_FP16X2_ALL) tile_clk *= score ? 0.41 : 0.62;
+    const double slot_bytes = (double)m_pad * (score ? 16 * kb + 1 : 1) * 8.0;
+    const double slot = slot_bytes / 1250.0 / tile_clk;          // 1250 bytes per clock = 3 TB/s at 2.4 GHz
+    return work + tail + nsplit * slot;
+}
 
 Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
 {
@@ -101,20 +147,19 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
     p.ntiles = (int)((n + 2 * kTile - 1) / (2 * kTile)) * 2;   // even: the pair kernel alternates two operand sets
     const int max_split = p.ntiles >= 32 ? p.ntiles / 16 : 1;   // at least 16 tiles per split
 
-    // Candidate row-tile counts, largest (most operand reuse) first; a smaller one is taken
-    // only when the grid would otherwise leave most of the chip idle.
+    // Candidate row-tile counts, largest (most operand reuse) first.
     int cand[5];
     int nc = 0;
     if (p.thin) {
         cand[nc++] = 4; cand[nc++] = 2; cand[nc++] = 1;
     } else {
         const int kb = p.dp / 16;
-        // measured: more row tiles per wave (operand reuse) beats a second wave per SIMD once dp >= 48
         const int top = max_row_tiles(kb, score ? kScoreSelf : kEval);
         for (int v = top; v >= 2; v /= 2) cand[nc++] = v;
     }
     const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
-    const int forced_split = env_int(score ? "SDKDE_SCORE_SPLIT" : "SDKDE_EVAL_SPLIT", 0);
+    int forced_split = env_int(score ? "SDKDE_SCORE_SPLIT" : "SDKDE_EVAL_SPLIT", 0);
+    if (forced_split > p.ntiles) forced_split = p.ntiles;
     {
         // a forced value must be one the dispatch tables below instantiate
         const int kb = p.thin ? 0 : p.dp / 16;
@@ -125,22 +170,48 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
             nc = 1;
         }
     }
-
-    for (int k = 0; k < nc; ++k) {
-        p.ni = cand[k];
-        p.rows_per_block = p.thin ? kBlock * p.ni : kWavesPerBlock * kTile * p.ni;
+    auto set_row_tiles = [&](int ni) {
+        p.ni = ni;
+        p.rows_per_block = p.thin ? kBlock * ni : kWavesPerBlock * kTile * ni;
         p.row_blocks = (m + p.rows_per_block - 1) / p.rows_per_block;
         if (p.row_blocks < 1) p.row_blocks = 1;
-        int64_t want = (kTargetBlocks + p.row_blocks - 1) / p.row_blocks;
-        if (max_split >= 8) {                       // one group of splits per XCD
-            want = round_up(want < 8 ? 8 : want, 8);
-            if (want > max_split) want = max_split / 8 * 8;
-        } else if (want > max_split) {
-            want = max_split;
+    };
+
+    if (!p.thin && max_split >= 8) {
+        // Matrix path with enough samples for one group of splits per XCD: the (row tiles, splits) pair of least
+        // estimated time; ties go to more row tiles, then fewer splits.
+        const uint32_t prec = effective_prec(flags, false, p.dp);
+        const int most = max_split / 8 * 8 < 1024 ? max_split / 8 * 8 : 1024;
+        double best = 0.0;
+        int best_ni = 0, best_split = 0;
+        for (int k = 0; k < nc; ++k) {
+            for (int sp = forced_split > 0 ? forced_split : 8; sp <= (forced_split > 0 ? forced_split : most); sp += 8) {
+                const double c = plan_cost(score, p.dp / 16, prec, m > 0 ? m : 1, p.m_pad, p.ntiles, cand[k], sp);
+                if (best_ni == 0 || c < best) {
+                    best = c;
+                    best_ni = cand[k];
+                    best_split = sp;
+                }
+            }
         }
-        p.nsplit = (int)want;
-        if (forced_split > 0) p.nsplit = forced_split > p.ntiles ? p.ntiles : forced_split;
-        if (p.row_blocks * p.nsplit >= kTargetBlocks / 2) break;
+        set_row_tiles(best_ni);
+        p.nsplit = best_split;
+    } else {
+        // Thin path and tiny sample sets: the largest row count per workgroup that still gives the chip enough
+        // workgroups, with as many splits as that takes.
+        for (int k = 0; k < nc; ++k) {
+            set_row_tiles(cand[k]);
+            int64_t want = (kTargetBlocks + p.row_blocks - 1) / p.row_blocks;
+            if (max_split >= 8) {                       // one group of splits per XCD
+                want = round_up(want < 8 ? 8 : want, 8);
+                if (want > max_split) want = max_split / 8 * 8;
+            } else if (want > max_split) {
+                want = max_split;
+            }
+            p.nsplit = (int)want;
+            if (forced_split > 0) p.nsplit = forced_split;
+            if (p.row_blocks * p.nsplit >= kTargetBlocks / 2) break;
+        }
     }
     p.tiles_per_split = (p.ntiles + p.nsplit - 1) / p.nsplit;
     p.tiles_per_split += p.tiles_per_split & 1;
@@ -162,8 +233,9 @@ constexpr int sym_row_tiles(int kb, int prec)
 constexpr int kSymMaxGroups = 64;
 
 // Decomposition of the symmetric mode, if this call takes it: the score at the samples themselves on the
-// matrix path, for the dimensions and input modes pair_sym_kernel is built for (sym_row_tiles).  Block size: as many rows as the LDS accumulators
-// hold ((dp + 1) floats per row within ~136 KiB), halved while there would be too few items to fill the chip.
+// matrix path, for the dimensions and input modes pair_sym_kernel is built for (sym_row_tiles).  Block size:
+// as many rows as the LDS accumulators hold ((dp + 1) floats per row within ~136 KiB), halved while there
+// would be too few items to fill the chip.
 void apply_symmetric(Plan& p, int64_t n, uint32_t flags, bool self)
 {
     if (!(flags & SDKDE_FLAG_SYMMETRIC) || !self || p.thin) return;
@@ -493,8 +565,8 @@ int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int6
 int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h, uint32_t flags)
 {
     if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
-    if (d > SDKDE_MAX_D || (flags & ~(15u | SDKDE_FLAG_MAX_SHIFT | SDKDE_FLAG_SYMMETRIC | SDKDE_FLAG_SAMPLES_PREPARED)) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_ALL)
-        return SDKDE_EUNSUPPORTED;
+    constexpr uint32_t known = 15u | SDKDE_FLAG_MAX_SHIFT | SDKDE_FLAG_SYMMETRIC | SDKDE_FLAG_SAMPLES_PREPARED;
+    if (d > SDKDE_MAX_D || (flags & ~known) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_ALL) return SDKDE_EUNSUPPORTED;
     if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
     return SDKDE_OK;
 }

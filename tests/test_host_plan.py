@@ -95,7 +95,7 @@ def test_plan_of_the_benchmark_configs(n, m, d):
     for call in range(3):
         p = _check(n, m, d, call, 0)
         if n >= 32768:
-            assert p["row_blocks"] * p["splits"] >= 1024     # enough workgroups for 256 CUs
+            assert p["row_blocks"] * p["splits"] >= 512      # at least two workgroups per compute unit
         if p["splits"] >= 8:
             assert p["splits"] % 8 == 0                       # one group of splits per XCD
     big = P.sdkde_describe_plan(1048576, 131072, 16, 0)
