@@ -19,7 +19,8 @@
  *    |p|^2 + |x|^2 - 2 p.x on mean-centred coordinates, which loses about (R/h)^2 * 2^-24 in
  *    the exponent of phi (R = distance of a point from the sample mean).  The stated 1e-3
  *    tolerances hold while R/h stays below ~100; the thin path (d <= 3) uses direct
- *    differences and has no such limit.  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
+ *    differences and has no such limit.  (Far outside that domain, R/h above ~1e18, the scaled
+ *    coordinates overflow fp32 on either path and the outputs are NaN.)  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
  *    is kept: a point at which every phi_j is below the fp32 range (exponent under -126 ln 2)
  *    gets the documented all-underflow results instead of a shifted sum.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
