@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 SOURCES = [os.path.join(HERE, "csrc", "sdkde.hip")]      # one translation unit; the kernels live in the headers
 HEADERS = [os.path.join(ROOT, "include", "sdkde.h")] + [
     os.path.join(HERE, "csrc", name)
-    for name in ("common.h", "prep.h", "pair_mfma.h", "pair_sym.h", "pair_thin.h", "epilogue.h")]
+    for name in ("common.h", "prep.h", "pair_mfma.h", "pair_lds.h", "pair_sym.h", "pair_thin.h", "epilogue.h")]
 LIBRARY = os.path.join(HERE, "libsdkde.so")
 PEAKS_SOURCE = os.path.join(HERE, "csrc", "peaks.hip")
 PEAKS_BINARY = os.path.join(HERE, "sdkde_peaks")     # micro-benchmark of the instruction rates that bound the kernels

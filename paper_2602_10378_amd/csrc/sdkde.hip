@@ -13,6 +13,7 @@
 #include "common.h"
 #include "prep.h"
 #include "pair_mfma.h"
+#include "pair_lds.h"
 #include "pair_sym.h"
 #include "pair_thin.h"
 #include "epilogue.h"
@@ -23,12 +24,18 @@ namespace {
 // Host side: plan, workspace layout, dispatch.
 // ------------------------------------------------------------------------------------------
 
-// Most row tiles per wave for which pair_mfma_kernel is instantiated (larger ones would spill registers).
+// Whether the kinds without a second contraction run pair_lds_kernel (sample tile staged in LDS) instead of
+// pair_mfma_kernel: fp32 inputs from dp = 64 on.  Measured (eval, n = 262144, m = 65536, best plan of each):
+// d = 32 9.44 against 9.10 ms (slower), d = 48 13.11 / 13.16, d = 64 16.79 / 17.57, d = 128 32.0 / 43.5 ms.
+constexpr bool lds_staged(int kb, int prec) { return prec == SDKDE_PREC_FP32 && kb >= 4; }
+
+// Most row tiles per wave for which the pair kernels are instantiated (larger ones would spill registers).
 constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
 {
     const bool second = kind == kScoreSelf || kind == kScorePoints || kind == kScoreBand;   // has the Phi X contraction
     if (prec == SDKDE_PREC_FP16X2_ALL && kb > 6) return 0;              // see effective_prec()
     if (kind == kScoreBand && (kb > 2 || prec != SDKDE_PREC_FP32)) return 0;          // see sym_row_tiles()
+    if (!second && lds_staged(kb, prec)) return 4;
     return second ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
 }
 
@@ -91,14 +98,19 @@ constexpr int kComputeUnits = 256;
 // best count (operand reuse against register pressure), measured on MI355X at n = 65536 .. 262144 with fp32
 // inputs: score d = 16: 2 / 4 / 8 row tiles 2.67 / 2.37 / 2.37 ms (n = 65536); d = 64: 2 / 4: 9.67 / 8.11 ms;
 // eval d = 16 (n = 262144, m = 65536): 2 / 4 / 8 / 16: 5.70 / 5.55 / 5.51 / 5.57 ms; d = 32: 2 / 4 / 8:
-// 9.57 / 9.21 / 9.10 ms; d = 64: 2 / 4: 20.8 / 17.6 ms.
-double row_tiles_penalty(bool score, int kb, int ni)
+// 9.57 / 9.21 / 9.10 ms; d = 48: 2 / 4: 14.3 / 13.1 ms; d = 64 and 128 (pair_lds_kernel): 2 / 4: 16.9 / 16.8 and
+// 32.5 / 32.0 ms.
+double row_tiles_penalty(bool score, int kb, int ni, uint32_t prec)
 {
-    if (kb >= 5) return 1.0;                                  // only ni = 2 is built
-    if (score) return ni >= 8 ? 1.0 : ni == 4 ? (kb == 1 ? 1.004 : 1.0) : (kb == 1 ? 1.12 : 1.15);
+    if (score) {
+        if (kb >= 5) return 1.0;                              // only ni = 2 is built
+        return ni >= 8 ? 1.0 : ni == 4 ? (kb == 1 ? 1.004 : 1.0) : (kb == 1 ? 1.12 : 1.15);
+    }
     if (kb == 1) return ni == 16 ? 1.013 : ni == 8 ? 1.0 : ni == 4 ? 1.005 : 1.035;
     if (kb == 2) return ni == 8 ? 1.0 : ni == 4 ? 1.008 : 1.05;
-    return ni == 4 ? 1.0 : 1.17;
+    if (lds_staged(kb, (int)prec)) return ni == 4 ? 1.0 : 1.01;
+    if (kb >= 5) return 1.0;                                  // only ni = 2 is built
+    return ni == 4 ? 1.0 : kb == 3 ? 1.09 : 1.17;
 }
 
 // Estimated time of the pair kernel plus its share of the epilogue for `ni` row tiles per wave and `nsplit`
@@ -116,11 +128,7 @@ double plan_cost(bool score, int kb, uint32_t prec, int64_t m, int64_t m_pad, in
     const int64_t rounds = (groups + kComputeUnits - 1) / kComputeUnits;
     int tps = (ntiles + nsplit - 1) / nsplit;
     tps += tps & 1;
-    double work = (double)rounds * ni * (tps + 1.0) * row_tiles_penalty(score, kb, ni);
-    // two row tiles per wave at d >= 49 re-read the sample tiles from L2 four times per workgroup: a lone
-    // workgroup per compute unit keeps them in the vector cache (measured 0.36 against 0.43 ms at d = 128,
-    // n = 32768, m = 4096)
-    if (ni == 2 && kb >= 4 && groups <= kComputeUnits) work *= 0.85;
+    const double work = (double)rounds * ni * (tps + 1.0) * row_tiles_penalty(score, kb, ni, prec);
     const double tail = 0.1 * ni * tps;
     // clocks per tile: the MFMAs at their measured issue time (33 clocks in fp32; the fp16 modes in proportion to
     // their measured kernel times), plus exp and sums
@@ -154,7 +162,7 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
         cand[nc++] = 4; cand[nc++] = 2; cand[nc++] = 1;
     } else {
         const int kb = p.dp / 16;
-        const int top = max_row_tiles(kb, score ? kScoreSelf : kEval);
+        const int top = max_row_tiles(kb, score ? kScoreSelf : kEval, (int)effective_prec(flags, false, p.dp));
         for (int v = top; v >= 2; v /= 2) cand[nc++] = v;
     }
     const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
@@ -163,7 +171,7 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
     {
         // a forced value must be one the dispatch tables below instantiate
         const int kb = p.thin ? 0 : p.dp / 16;
-        const int widest = p.thin ? 4 : max_row_tiles(kb, score ? kScoreSelf : kEval);
+        const int widest = p.thin ? 4 : max_row_tiles(kb, score ? kScoreSelf : kEval, (int)effective_prec(flags, false, p.dp));
         const int narrowest = p.thin ? 1 : 2;
         if (forced_ni >= narrowest && forced_ni <= widest && (forced_ni & (forced_ni - 1)) == 0) {
             cand[0] = forced_ni;
@@ -390,6 +398,26 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
             case 32: SDKDE_LAUNCH_THIN(3, 2); break;
             case 31: SDKDE_LAUNCH_THIN(3, 1); break;
             default: return SDKDE_EUNSUPPORTED;
+        }
+    } else if (lds_staged(p.dp / 16, PREC) && (KIND == kEval || KIND == kEvalLaplace || KIND == kRowMax)) {
+        if constexpr (PREC == SDKDE_PREC_FP32 && (KIND == kEval || KIND == kEvalLaplace || KIND == kRowMax)) {
+#define SDKDE_LAUNCH_LDS(KB_, NI_)                                                                                \
+    hipLaunchKernelGGL((pair_lds_kernel<KB_, NI_, KIND>), grid, block, 0, st, w.ps, w.pn, w.xs, w.xn, w.part_d,   \
+                       p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad, laplace_c0, shift)
+#define SDKDE_CASE_LDS(KB_)                                                                   \
+    case KB_:                                                                                 \
+        switch (p.ni) {                                                                       \
+            case 2: SDKDE_LAUNCH_LDS(KB_, 2); break;                                          \
+            case 4: SDKDE_LAUNCH_LDS(KB_, 4); break;                                          \
+            default: return SDKDE_EUNSUPPORTED;                                               \
+        }                                                                                     \
+        break;
+            switch (p.dp / 16) {
+                SDKDE_CASE_LDS(4) SDKDE_CASE_LDS(5) SDKDE_CASE_LDS(6) SDKDE_CASE_LDS(7) SDKDE_CASE_LDS(8)
+                default: return SDKDE_EUNSUPPORTED;
+            }
+#undef SDKDE_CASE_LDS
+#undef SDKDE_LAUNCH_LDS
         }
     } else {
         const int kb = p.dp / 16;
@@ -690,7 +718,8 @@ int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_
     apply_symmetric(self_plan, n, flags, true);
     size_t need = layout(self_plan, true, false, nullptr, flags).bytes;
     if (m > 0) {
-        size_t b = layout(make_plan(n, m, d, true, flags), true, true, nullptr, flags).bytes;
+        const uint32_t at_points = anchored_flags(flags, false);      // the mode a score at separate points runs in
+        size_t b = layout(make_plan(n, m, d, true, at_points), true, true, nullptr, at_points).bytes;
         need = b > need ? b : need;
         b = layout(make_plan(n, m, d, false, flags), false, true, nullptr, flags).bytes;
         need = b > need ? b : need;

@@ -116,6 +116,33 @@ def test_laplace_corrected_kde_matches_oracle(lib, n, m, d, seed):
 
 # fp16x2 input mode (inputs of the distance cross term split into two fp16 halves): a
 # lower-precision-input mode, held to the same tolerances and with its error printed separately.
+@pytest.mark.parametrize("d", [64, 70, 90, 112, 128])
+@pytest.mark.parametrize("row_tiles", [2, 4])
+def test_eval_kinds_at_large_dimension(lib, d, row_tiles, monkeypatch):
+    """From dp = 64 on the kinds without a second contraction run the kernel that stages the sample tile in
+    LDS: plain, Laplace-corrected and max-shifted eval over several splits, with a ragged last tile and
+    tiles of 320 / 384 / 448 / 512 float4s (not all multiples of the workgroup size)."""
+    P, torch = lib
+    n, m = 4500 + d, 301
+    print(f"large-d eval kinds n={n} m={m} d={d} row tiles {row_tiles}", flush=True)
+    monkeypatch.setenv("SDKDE_EVAL_NI", str(row_tiles))       # both instantiations (the plan takes 2 at this size)
+    x, q, h = _mixture(n, m, d, 70 + d)
+    h = float(h) * (2.0 if d > 64 else 1.2)       # keep the sums inside the fp32 range without a shift
+    plan = P.sdkde_describe_plan(n, m, d, 2)
+    assert plan["splits"] >= 8 and plan["row_tiles"] == row_tiles
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ref = oracle.eval_log_density(x, q, h)
+    lref, labs = oracle.eval_laplace_density(x, q, h), oracle.eval_laplace_abs_density(x, q, h)
+    for flags in (0, P.SDKDE_FLAG_MAX_SHIFT):
+        _, logd = P.sdkde_eval(xd, qd, h, want="log", flags=flags)
+        assert_log_density_close(logd.cpu().numpy(), ref, f"large-d eval d={d} flags={flags}")
+        lap = P.sdkde_eval_laplace(xd, qd, h, flags=flags).cpu().numpy()
+        assert_laplace_close(lap, lref, labs, f"large-d laplace d={d} flags={flags}")
+    # the score at separate points with the shift takes its row maxima from the same kernel
+    sp = P.sdkde_score(xd, h, points=qd, flags=P.SDKDE_FLAG_MAX_SHIFT).cpu().numpy()
+    assert_score_close(sp, oracle.score(x, h, points=q), f"large-d shifted score d={d}")
+
+
 @pytest.mark.parametrize("mode", [1, 2])
 @pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (1200, 200, 5, 6), (1100, 130, 20, 7),
                                         (2048, 512, 64, 10), (700, 90, 100, 11), (17, 9, 16, 2), (3000, 500, 1, 0)])

@@ -150,21 +150,26 @@ def test_profile_instrumentation_counts_launches_on_the_callers_stream():
             P.sdkde_score(xd, h, out=score, workspace=ws)
     torch.cuda.synchronize()
     P.sdkde_profile_enable(False)
-    P.sdkde_profile_enable(True)                       # starts an empty record
-    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    with torch.cuda.stream(side):
-        t0.record()
-        for _ in range(3):
-            P.sdkde_score(xd, h, out=score, workspace=ws)
-        t1.record()
-        P.sdkde_eval(xd, qd, h, workspace=ws)
-    torch.cuda.synchronize()
-    n_score, ms_score = P.sdkde_profile_summary(0)
-    n_eval, ms_eval = P.sdkde_profile_summary(1)
-    P.sdkde_profile_enable(False)
-    assert (n_score, n_eval) == (3, 1)
-    assert 0.0 < ms_score <= t0.elapsed_time(t1) and ms_eval > 0.0
-    assert ms_score > 0.5 * t0.elapsed_time(t1)        # the pair kernel dominates a call of this size
+    # The stream events also see whatever pause the host takes between two launches (a garbage collection,
+    # a page fault), so the comparison with them is made on the best of a few repetitions.
+    share = 0.0
+    for rep in range(5):
+        P.sdkde_profile_enable(True)                   # starts an empty record
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            t0.record()
+            for _ in range(3):
+                P.sdkde_score(xd, h, out=score, workspace=ws)
+            t1.record()
+            P.sdkde_eval(xd, qd, h, workspace=ws)
+        torch.cuda.synchronize()
+        n_score, ms_score = P.sdkde_profile_summary(0)
+        n_eval, ms_eval = P.sdkde_profile_summary(1)
+        P.sdkde_profile_enable(False)
+        assert (n_score, n_eval) == (3, 1)
+        assert 0.0 < ms_score <= t0.elapsed_time(t1) and ms_eval > 0.0
+        share = max(share, ms_score / t0.elapsed_time(t1))
+    assert share > 0.5                                 # the pair kernel dominates a call of this size
     assert P.sdkde_profile_summary(0) == (0, 0.0)      # disabling reset the record
 
 
