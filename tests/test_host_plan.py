@@ -104,6 +104,23 @@ def test_plan_of_the_benchmark_configs(n, m, d):
     assert (sym["sym_block_rows"], sym["sym_blocks_per_group"], sym["sym_groups"]) == (2048, 8, 64)
 
 
+@pytest.mark.parametrize("n,m,d,call", [(20000, 20000, 16, 0), (12288, 12288, 16, 0), (32768, 4096, 16, 0),
+                                        (32768, 4096, 16, 2), (262144, 20000, 16, 2), (1048576, 131072, 16, 2),
+                                        (262144, 65536, 64, 0), (262144, 65536, 128, 2), (100000, 100000, 16, 0),
+                                        (40000, 40000, 32, 0), (50000, 50000, 128, 0)])
+def test_plan_fills_the_last_round_of_workgroups(n, m, d, call):
+    """The plan is the (row tiles, splits) pair of least estimated time; with enough samples to choose from, the
+    workgroups must come close to a whole number of rounds over the 256 compute units (a count just above a
+    multiple of 256 would leave most of the chip idle for a round), without paying for more splits than that takes."""
+    p = _check(n, m, d, call, 0)
+    groups = p["row_blocks"] * p["splits"]
+    rounds = -(-groups // 256)
+    assert groups >= 512 and groups / (256 * rounds) >= 0.97
+    assert p["splits"] % 8 == 0 and p["tiles_per_split"] >= 16
+    if call == 0:
+        assert p["splits"] <= 32          # every split costs a slot of partial T and D sums
+
+
 def test_describe_plan_rejects_bad_arguments():
     for args in ((0, 1, 16, 0, 0), (10, 10, 16, 3, 0), (10, 10, 200, 0, 0), (10, 10, 16, 0, 99)):
         with pytest.raises(P.SdkdeError):
