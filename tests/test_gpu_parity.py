@@ -203,7 +203,8 @@ def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
 
 # Evaluating one fitted estimate at batch after batch of queries: with SDKDE_FLAG_SAMPLES_PREPARED the samples
 # prepared by the previous eval call on the same workspace are reused; the results must be the bits of a fresh call.
-@pytest.mark.parametrize("n,d,flags", [(5000, 16, 0), (3000, 2, 0), (4000, 7, 0), (2500, 20, 1), (3000, 16, 16), (2000, 40, 17)])
+@pytest.mark.parametrize("n,d,flags", [(5000, 16, 0), (3000, 2, 0), (4000, 7, 0), (2500, 20, 1), (3000, 16, 16), (2000, 40, 17),
+                                       (2500, 70, 0)])
 def test_eval_with_samples_prepared_by_the_previous_call(lib, n, d, flags):
     P, torch = lib
     print(f"samples prepared n={n} d={d} flags={flags}", flush=True)
