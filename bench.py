@@ -194,6 +194,14 @@ def main():
         out["roofline"] = {"bound": "alu", "achieved": ach, "peak": peak, "unit": "T lane-slots/s", "frac": ach / peak,
                            "traffic": None, "kernel": "pair_thin_kernel (score)", "launch_ms": score_avg_ms,
                            "slots_per_pair": 3 * d + 3}
+    if not P.sdkde_describe_plan(n, m, d, 2)["thin"]:
+        # the second kernel of the step, for completeness: 2d flops per pair (the cross term only); per tile 4 d/16
+        # MFMAs against the same VALU work as the score kernel
+        eval_tflops = 2.0 * d * float(m) * n / (eval_avg_ms * 1e-3) / 1e12
+        out["roofline_eval_kernel"] = {"bound": "mfma", "achieved": eval_tflops, "peak": PEAK_FP32_MFMA_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": eval_tflops / PEAK_FP32_MFMA_TFLOPS,
+                                       "launch_ms": eval_avg_ms,
+                                       "frac_ceiling_of_instruction_mix": (128.0 * d / 16) / (128.0 * d / 16 + 4 * 8 + 8 * 4 + 6)}
     if other:
         out["other_modes"] = other
     if not args.no_cpu_baseline:
