@@ -61,6 +61,34 @@ struct PrepJob {
     float pad_value;      // thin path only: coordinate value of padding rows
 };
 
+// Record of what a prep launch left in the workspace (sample arrays and column sums), kept in the workspace itself:
+// a launch that prepares samples writes it, a launch that relies on earlier samples (SDKDE_FLAG_SAMPLES_PREPARED)
+// compares it with what it expects and, on a mismatch, poisons its own outputs with NaN so that every result of the
+// call is NaN instead of a plausible number from someone else's samples.
+constexpr int kStampWords = 6;
+struct Stamp {
+    uint64_t* where;                // in the workspace; null: no record kept or checked
+    int check;                      // 0: write `value` (workgroup 0), 1: compare with `value`
+    uint64_t value[kStampWords];    // kind of call, samples pointer, n, d, precision mode, bits of the scale a
+};
+
+// Thread 0 of every workgroup reads or (workgroup 0) writes the record; returns whether this launch is poisoned.
+// Ends with a barrier.
+__device__ __forceinline__ bool stamp_poisons(const Stamp& stamp, int* flag)
+{
+    if (threadIdx.x == 0) {
+        int bad = 0;
+        if (stamp.where && stamp.check) {
+            for (int k = 0; k < kStampWords; ++k) bad |= stamp.where[k] != stamp.value[k];
+        } else if (stamp.where && blockIdx.x == 0) {
+            for (int k = 0; k < kStampWords; ++k) stamp.where[k] = stamp.value[k];
+        }
+        *flag = bad;
+    }
+    __syncthreads();
+    return *flag != 0;
+}
+
 constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (two 16-sample tiles; 2 x 16.5 KiB of LDS)
 
 // Centre, scale and pad for the MFMA path.  A workgroup stages kPrepRows rows in LDS and writes
@@ -77,12 +105,14 @@ constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (tw
 // Grid: job0's blocks first (blocks0 of them), then job1's; sample mean from mean_partial.
 __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
                                                            const double* __restrict__ mean_partial, int64_t n_mean,
-                                                           float a, int prec)
+                                                           float a, int prec, Stamp stamp)
 {
     __shared__ double red[kBlock];
     __shared__ float smean[SDKDE_MAX_D];
     __shared__ float raw[kPrepRows][SDKDE_MAX_D + 1];     // a (x - mean)
     __shared__ float used[kPrepRows][SDKDE_MAX_D + 1];    // the value the first contraction multiplies (hi + lo, or raw)
+    __shared__ int stamp_flag;
+    const bool poisoned = stamp_poisons(stamp, &stamp_flag);
     block_mean(mean_partial, d, n_mean, red, smean);
 
     const bool second = (int)blockIdx.x >= blocks0;
@@ -130,7 +160,7 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
         double acc = 0.0;
         for (int c = 0; c < dp; ++c) acc += (double)used[threadIdx.x][c] * (double)used[threadIdx.x][c];
         const int64_t row = r0 + threadIdx.x;
-        job.dst_n[row] = row < job.rows ? -(float)acc : kPadNorm;
+        job.dst_n[row] = poisoned ? __builtin_nanf("") : row < job.rows ? -(float)acc : kPadNorm;
     }
 }
 
@@ -138,17 +168,19 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
 // One thread per padded row; same two-job grid.
 __global__ __launch_bounds__(kBlock) void prep_thin_kernel(PrepJob job0, PrepJob job1, int blocks0, int d,
                                                            const double* __restrict__ mean_partial, int64_t n_mean,
-                                                           float a)
+                                                           float a, Stamp stamp)
 {
     __shared__ double red[kBlock];
     __shared__ float smean[SDKDE_MAX_D];
+    __shared__ int stamp_flag;
+    const bool poisoned = stamp_poisons(stamp, &stamp_flag);
     block_mean(mean_partial, d, n_mean, red, smean);
     const bool second = (int)blockIdx.x >= blocks0;
     const PrepJob& job = second ? job1 : job0;
     const int64_t row = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kBlock + threadIdx.x;
     if (row >= job.rows_pad) return;
     for (int c = 0; c < d; ++c)
-        job.dst[row * d + c] = row < job.rows ? a * (job.src[row * d + c] - smean[c]) : job.pad_value;
+        job.dst[row * d + c] = poisoned ? __builtin_nanf("") : row < job.rows ? a * (job.src[row * d + c] - smean[c]) : job.pad_value;
 }
 
 }  // namespace

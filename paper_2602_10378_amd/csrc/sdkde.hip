@@ -10,6 +10,7 @@
 // The cross term is the Gram-matrix tile of the Method section, computed with fp32 MFMA;
 // the score numerator uses Phi X with the Phi tile still in the registers the first MFMA
 // left it in.
+#include <string.h>
 #include "common.h"
 #include "prep.h"
 #include "pair_mfma.h"
@@ -286,6 +287,7 @@ void apply_symmetric(Plan& p, int64_t n, uint32_t flags, bool self)
 
 struct Workspace {
     double* mean_partial;
+    uint64_t* stamp;                       // record of the last sample preparation (prep.h)
     float* xs;  float* xt;  float* xn;     // samples: scaled rows, blocked transpose, -|x|^2
     float* ps;  float* pn;                 // evaluation points (alias xs/xn when they are the samples)
     float* shift;                          // per-point exponent shift of the max-shifted mode (separate points only)
@@ -305,6 +307,7 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base, ui
         return base ? (char*)base + at : (char*)nullptr;
     };
     w.mean_partial = (double*)take(sizeof(double) * kMeanBlocks * SDKDE_MAX_D);
+    w.stamp = (uint64_t*)take(sizeof(uint64_t) * kStampWords);
     w.xs = (float*)take(sizeof(float) * p.n_pad * p.dp);
     // blocked transpose for the second contraction: fp32, or hi/lo fp16 pairs stored twice (2x the bytes)
     const size_t xt_scale = effective_prec(flags, p.thin, p.dp) == SDKDE_PREC_FP16X2_ALL ? 2 : 1;
@@ -572,8 +575,22 @@ int launch_mean(const float* src, int64_t rows, int d, const Workspace& w, hipSt
 
 // Centre/scale/pad one or two arrays in a single launch (second.src == nullptr: only the first).
 // n_mean: number of rows the column means in w.mean_partial were taken over.
+// What identifies prepared samples: the kind of call that prepared them (the score and eval layouts differ), the
+// caller's array, its shape, the precision mode and the scale a = sqrt(log2 e / 2) / h as it reached the kernels.
+Stamp make_stamp(const Workspace& w, bool check, bool score, const float* samples, int64_t n, int d, uint32_t prec, float a)
+{
+    Stamp s{};
+    s.where = w.stamp;
+    s.check = check ? 1 : 0;
+    uint32_t abits;
+    memcpy(&abits, &a, sizeof abits);
+    const uint64_t v[kStampWords] = {score ? 1u : 2u, (uint64_t)(uintptr_t)samples, (uint64_t)n, (uint64_t)d, prec, abits};
+    for (int k = 0; k < kStampWords; ++k) s.value[k] = v[k];
+    return s;
+}
+
 int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int64_t n_mean, float a,
-                const Workspace& w, uint32_t flags, hipStream_t st)
+                const Workspace& w, uint32_t flags, const Stamp& stamp, hipStream_t st)
 {
     const int64_t per_block = p.thin ? kBlock : kPrepRows;
     if (first.rows_pad % per_block || (second.src && second.rows_pad % per_block)) return SDKDE_EINVAL;
@@ -583,10 +600,10 @@ int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int6
     const dim3 grid((unsigned)(blocks0 + blocks1)), block(kBlock);
     if (p.thin)
         hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, w.mean_partial,
-                           n_mean, a);
+                           n_mean, a, stamp);
     else
         hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, p.dp,
-                           w.mean_partial, n_mean, a, (int)effective_prec(flags, p.thin, p.dp));
+                           w.mean_partial, n_mean, a, (int)effective_prec(flags, p.thin, p.dp), stamp);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
@@ -639,7 +656,8 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
     const PrepJob sample_job{samples, n, p.n_pad, w.xs, w.xt, w.xn, kPadCoord};
     const PrepJob point_job{self ? nullptr : points, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
-    if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+    const Stamp stamp = make_stamp(w, false, true, samples, n, d, effective_prec(flags, p.thin, p.dp), (float)a);
+    if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, stamp, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
     // at the samples themselves the largest weight is the self pair (exponent 0): nothing to shift
@@ -684,10 +702,13 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if (flags & SDKDE_FLAG_SAMPLES_PREPARED) {
         // the workspace still holds the column sums and the prepared samples (their place in the workspace depends
         // on n, d and the precision mode only, not on m): only the queries are prepared
-        if ((rc = launch_prep(p, query_job, PrepJob{}, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+        // (a call whose record of the prepared samples does not match gets NaN for every output)
+        const Stamp expect = make_stamp(w, true, false, samples, n, d, effective_prec(flags, p.thin, p.dp), (float)a);
+        if ((rc = launch_prep(p, query_job, PrepJob{}, n, (float)a, w, flags, expect, st)) != SDKDE_OK) return rc;
     } else {
         if (!reuse_mean && (rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
-        if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, st)) != SDKDE_OK) return rc;
+        const Stamp stamp = make_stamp(w, false, false, samples, n, d, effective_prec(flags, p.thin, p.dp), (float)a);
+        if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, stamp, st)) != SDKDE_OK) return rc;
     }
 
     if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;

@@ -228,6 +228,19 @@ def test_eval_with_samples_prepared_by_the_previous_call(lib, n, d, flags):
     with pytest.raises(P.SdkdeError) as e:
         P.sdkde_score(xd, h, workspace=ws, flags=prepared)
     assert e.value.status == 2
+    # A call whose precondition does not hold is answered with NaN in every output, not with numbers that belong
+    # to other samples: another bandwidth, another sample array, a workspace last used by a score call, and a
+    # workspace that never saw a preparation.
+    qb = batches[0]
+    def all_nan(result):
+        return all(bool(torch.isnan(t).all()) for t in result)
+    assert not all_nan(P.sdkde_eval(xd, qb, h, want="both", workspace=ws, flags=prepared))
+    assert all_nan(P.sdkde_eval(xd, qb, h * 1.01, want="both", workspace=ws, flags=prepared))
+    assert all_nan(P.sdkde_eval(xd.clone(), qb, h, want="both", workspace=ws, flags=prepared))
+    assert all_nan([P.sdkde_eval_laplace(xd[:-1], qb, h, workspace=ws, flags=prepared)])
+    P.sdkde_score(xd, h, workspace=ws, flags=flags)
+    assert all_nan(P.sdkde_eval(xd, qb, h, want="both", workspace=ws, flags=prepared))
+    assert all_nan(P.sdkde_eval(xd, qb, h, want="both", workspace=torch.zeros_like(ws), flags=prepared))
     with pytest.raises(ValueError):
         P.sdkde_eval(xd, batches[0], h, flags=prepared)
 
