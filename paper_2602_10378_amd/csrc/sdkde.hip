@@ -91,7 +91,7 @@ int env_int(const char* name, int fallback)
     return atoi(v);
 }
 
-// Workgroups needed to keep 256 CUs busy with a few waves per SIMD (thin path and tiny problems).
+// Workgroups needed to keep 256 CUs busy with a few waves per SIMD (tiny problems).
 constexpr int64_t kTargetBlocks = 2048;
 constexpr int kComputeUnits = 256;
 
@@ -141,6 +141,27 @@ double plan_cost(bool score, int kb, uint32_t prec, int64_t m, int64_t m_pad, in
     return work + tail + nsplit * slot;
 }
 
+// The same estimate for the thin path (rows per thread `r`, 256 r rows per workgroup), in units of one thread's
+// time for one row against one 16-sample tile.  One row per thread is the fastest form per pair (measured at
+// n = 262144: d = 1 score 9.96 / 10.36 / 10.23 ms with 1 / 2 / 4 rows, d = 3 18.2 / 18.7 / 19.8 ms), and the
+// tail weighs more than on the matrix path; fitted to sweeps at d = 1 and 3, n = 8192 .. 1048576: the pick is
+// within 0.2 % of the best measured pair on average (1.3 % at worst), the earlier rule was 7 % off on average.
+double plan_cost_thin(bool score, int d, int64_t m, int64_t m_pad, int ntiles, int r, int nsplit)
+{
+    const int64_t row_blocks = (m + (int64_t)kBlock * r - 1) / ((int64_t)kBlock * r);
+    const int64_t groups = row_blocks * nsplit;
+    const int64_t rounds = (groups + kComputeUnits - 1) / kComputeUnits;
+    int tps = (ntiles + nsplit - 1) / nsplit;
+    tps += tps & 1;
+    const double penalty = r == 1 ? 1.0 : r == 2 ? 1.0 + 0.015 * (1 + d) : 1.0 + 0.03 * d;
+    const double work = (double)rounds * r * (tps + 1.0) * penalty;
+    const double tail = 0.6 * r * tps;
+    // clocks per row and tile: 16 pairs of 3d + 3 (score) or 2d + 3 (eval) VALU issue slots of 4 clocks
+    const double tile_clk = 64.0 * (score ? 3 * d + 3 : 2 * d + 3);
+    const double slot = (double)m_pad * (score ? d + 1 : 1) * 8.0 / 1250.0 / tile_clk;
+    return work + tail + nsplit * slot;
+}
+
 Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
 {
     Plan p{};
@@ -186,16 +207,17 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
         if (p.row_blocks < 1) p.row_blocks = 1;
     };
 
-    if (!p.thin && max_split >= 8) {
-        // Matrix path with enough samples for one group of splits per XCD: the (row tiles, splits) pair of least
-        // estimated time; ties go to more row tiles, then fewer splits.
+    if (max_split >= 8) {
+        // Enough samples for one group of splits per XCD: the (row tiles or rows per thread, splits) pair of least
+        // estimated time; ties go to more rows per workgroup, then fewer splits.
         const uint32_t prec = effective_prec(flags, false, p.dp);
         const int most = max_split / 8 * 8 < 1024 ? max_split / 8 * 8 : 1024;
         double best = 0.0;
         int best_ni = 0, best_split = 0;
         for (int k = 0; k < nc; ++k) {
             for (int sp = forced_split > 0 ? forced_split : 8; sp <= (forced_split > 0 ? forced_split : most); sp += 8) {
-                const double c = plan_cost(score, p.dp / 16, prec, m > 0 ? m : 1, p.m_pad, p.ntiles, cand[k], sp);
+                const double c = p.thin ? plan_cost_thin(score, d, m > 0 ? m : 1, p.m_pad, p.ntiles, cand[k], sp)
+                                        : plan_cost(score, p.dp / 16, prec, m > 0 ? m : 1, p.m_pad, p.ntiles, cand[k], sp);
                 if (best_ni == 0 || c < best) {
                     best = c;
                     best_ni = cand[k];
@@ -206,8 +228,8 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
         set_row_tiles(best_ni);
         p.nsplit = best_split;
     } else {
-        // Thin path and tiny sample sets: the largest row count per workgroup that still gives the chip enough
-        // workgroups, with as many splits as that takes.
+        // Tiny sample sets: the largest row count per workgroup that still gives the chip enough workgroups,
+        // with as many splits as that takes.
         for (int k = 0; k < nc; ++k) {
             set_row_tiles(cand[k]);
             int64_t want = (kTargetBlocks + p.row_blocks - 1) / p.row_blocks;
