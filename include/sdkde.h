@@ -67,8 +67,8 @@ enum {
                                then at most n 2^-39 max_j |x_j - mean| / h^2 on top of the FP16X2 mode's;
                                only a data set in which nearly every sample is isolated (all neighbour
                                weights under ~1e-7) has scores that small.  A score at separate points
-                               without the shift, and calls without a Phi X contraction (eval), run as
-                               FP16X2. */
+                               without the shift, calls without a Phi X contraction (eval), and d > 16
+                               (where it is no faster than FP16X2) run as FP16X2. */
     /* flags bit 4: two-pass, max-shifted sums for sdkde_eval, sdkde_eval_laplace and sdkde_score at
        separate points: a first pass finds max_j of the exponent for every point, the second sums
        phi_j / max phi, and the logarithm (or the signed density) gets the shift back.  Results then stay

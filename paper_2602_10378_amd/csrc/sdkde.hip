@@ -34,7 +34,7 @@ constexpr bool lds_staged(int kb, int prec) { return prec == SDKDE_PREC_FP32 && 
 constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
 {
     const bool second = kind == kScoreSelf || kind == kScorePoints || kind == kScoreBand;   // has the Phi X contraction
-    if (prec == SDKDE_PREC_FP16X2_ALL && kb > 6) return 0;              // see effective_prec()
+    if (prec == SDKDE_PREC_FP16X2_ALL && kb > 1) return 0;              // see effective_prec()
     if (kind == kScoreBand && (kb > 2 || prec != SDKDE_PREC_FP32)) return 0;          // see sym_row_tiles()
     if (!second && lds_staged(kb, prec)) return 4;
     return second ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
@@ -49,12 +49,14 @@ constexpr bool partial_last_block_built(int kb, int kind, int prec)
 }
 
 // Precision mode a call actually runs in: the thin path is fp32 VALU code; the fp16 second contraction is
-// built for dp <= 96 (beyond that its operands no longer fit the register file) and falls back to fp16x2.
+// used at dp = 16 only and falls back to fp16x2 above.  (Its split of Phi is VALU work that eight row tiles per
+// wave amortise best, and from dp = 32 on only four fit: measured at n = 131072, fp16x2 against fp16x2-all,
+// d = 32 10.7 / 11.3 ms and d = 64 21.7 / 22.3 ms, where d = 16 gives 6.0 / 4.4 ms.)
 inline uint32_t effective_prec(uint32_t flags, bool thin, int dp)
 {
     const uint32_t prec = flags & 15u;
     if (thin) return SDKDE_PREC_FP32;
-    if (prec == SDKDE_PREC_FP16X2_ALL && dp > 96) return SDKDE_PREC_FP16X2;
+    if (prec == SDKDE_PREC_FP16X2_ALL && dp > 16) return SDKDE_PREC_FP16X2;
     return prec;
 }
 
@@ -103,6 +105,18 @@ constexpr int kComputeUnits = 256;
 // 32.5 / 32.0 ms.
 double row_tiles_penalty(bool score, int kb, int ni, uint32_t prec)
 {
+    if (prec != SDKDE_PREC_FP32) {
+        // fp16 input modes (n = 131072 resp. n = 262144, m = 65536): the cheap MFMAs leave the operand loads and
+        // the VALU work exposed, so few row tiles cost much more than with fp32 inputs.  Score, fp16x2: d = 16
+        // 2 / 4 / 8 row tiles 6.51 / 6.02 / 6.13 ms, d = 32 2 / 4: 12.1 / 10.7, d = 64: 24.0 / 21.7; fp16x2-all
+        // (d = 16 only): 9.88 / 5.25 / 4.36 ms.  Eval: d = 16 2 / 4 / 8 / 16: 3.01 / 2.41 / 2.27 / 2.95 ms,
+        // d = 32 2 / 4 / 8: 8.15 / 4.30 / 3.39, d = 64 2 / 4: 15.3 / 7.9 ms.
+        if (score && prec == SDKDE_PREC_FP16X2_ALL) return ni >= 8 ? 1.0 : ni == 4 ? 1.2 : 2.25;
+        if (score) return kb >= 5 ? 1.0 : kb == 1 ? (ni >= 8 ? 1.018 : ni == 4 ? 1.0 : 1.08) : (ni >= 4 ? 1.0 : 1.12);
+        if (kb == 1) return ni == 16 ? 1.32 : ni == 8 ? 1.0 : ni == 4 ? 1.065 : 1.33;
+        if (kb == 2) return ni == 8 ? 1.0 : ni == 4 ? 1.27 : 2.4;
+        return kb >= 5 ? 1.0 : ni == 4 ? 1.0 : 1.94;
+    }
     if (score) {
         if (kb >= 5) return 1.0;                              // only ni = 2 is built
         return ni >= 8 ? 1.0 : ni == 4 ? (kb == 1 ? 1.004 : 1.0) : (kb == 1 ? 1.12 : 1.15);
@@ -110,8 +124,7 @@ double row_tiles_penalty(bool score, int kb, int ni, uint32_t prec)
     if (kb == 1) return ni == 16 ? 1.013 : ni == 8 ? 1.0 : ni == 4 ? 1.005 : 1.035;
     if (kb == 2) return ni == 8 ? 1.0 : ni == 4 ? 1.008 : 1.05;
     if (lds_staged(kb, (int)prec)) return ni == 4 ? 1.0 : 1.01;
-    if (kb >= 5) return 1.0;                                  // only ni = 2 is built
-    return ni == 4 ? 1.0 : kb == 3 ? 1.09 : 1.17;
+    return ni == 4 ? 1.0 : 1.09;                              // kb = 3
 }
 
 // Estimated time of the pair kernel plus its share of the epilogue for `ni` row tiles per wave and `nsplit`
