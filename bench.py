@@ -123,7 +123,9 @@ def main():
                                "fp32 accumulate, exp and row sums fp32",
                  "symmetric_score": "fp32 path; the score computes each unordered pair of samples once (phi_ij = phi_ji) "
                                     "and is still counted as n^2 pairs, as the paper counts them"}
-        modes = [("fp16x2_inputs", P.SDKDE_PREC_FP16X2), ("fp16x2_all", P.SDKDE_PREC_FP16X2_ALL)]
+        modes = [("fp16x2_inputs", P.SDKDE_PREC_FP16X2)]
+        if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_PREC_FP16X2_ALL)["xt_scale"] == 2:      # else it runs as fp16x2 (d > 16)
+            modes.append(("fp16x2_all", P.SDKDE_PREC_FP16X2_ALL))
         if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_FLAG_SYMMETRIC)["symmetric"]:
             modes.append(("symmetric_score", P.SDKDE_FLAG_SYMMETRIC))
         for key, flags in modes:
