@@ -88,3 +88,16 @@ def test_product_package_never_references_the_oracle():
         for name in files:
             if name.endswith((".py", ".hip", ".h")):
                 assert "oracle" not in open(os.path.join(dirpath, name)).read(), f"{name} mentions the oracle"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is single-GPU by design: asking for more must end with a message, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for extra_env, args in (({}, ["--gpus", "2"]), ({"WORLD_SIZE": "2"}, [])):
+        env = dict(os.environ, **extra_env)
+        proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), *args], env=env, capture_output=True, text=True,
+                              timeout=120)
+        assert proc.returncode != 0
+        assert "single-GPU" in (proc.stderr + proc.stdout)

@@ -9,7 +9,7 @@ import sdkde_inputs
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,n,m,flags", [("C1", 4096, 1024, 0), ("C3", 5000, 700, 0), ("C1", 5000, 700, 32)])
+@pytest.mark.parametrize("name,n,m,flags", [("C1", 4096, 1024, 0), ("C3", 5000, 700, 0), ("C1", 5000, 700, 32), ("C4", 3000, 500, 0)])
 def test_pipeline_replays_from_a_graph(name, n, m, flags, monkeypatch):
     import torch
     monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")      # take the symmetric mode at this small size too
