@@ -203,17 +203,21 @@ def main():
                            "frac_ceiling_of_instruction_mix": (256.0 * d / 16) / (256.0 * d / 16 + 4 * 8 + 8 * 4 + 13),
                            "valu": {"exp_per_s": float(n) * n / (score_avg_ms * 1e-3),
                                     "peak_exp_per_s": 256 * 4 * 16 * 2.4e9 / 2.0,
-                                    "note": "v_exp_f32 at half rate (8 clocks per wave instruction); sdkde_peaks measures 14.8e12/s back to back"}}
+                                    "note": "v_exp_f32: 8 clocks per wave instruction; sdkde_peaks measures 19.4e12/s back to back"}}
     else:
-        # thin-d path (Appendix A): VALU-issue bound.  Per score pair: d subs + d FMAs (r^2) + 1 add (D) + d FMAs
-        # (numerator) + one v_exp_f32, which issues at half rate (2 slots).  Peak = 256 CUs x 4 SIMDs x 16 lanes x
-        # 2.4 GHz = 39.3 T lane-slots/s (fp32 VALU without packed math; 78.6 TFLOP/s counting an FMA as 2 flops).
-        slots = (3 * d + 1 + 2) * float(n) * n
-        peak = 256 * 4 * 16 * 2.4e9 / 1e12
+        # thin-d path (Appendix A): VALU bound.  Per score pair: d subs + d FMAs (r^2) + 1 add (D) + d FMAs
+        # (numerator) = 3d + 1 plain instructions, and one v_exp_f32 at a quarter of their rate (4 slots).  Peak:
+        # the chip's fp32 vector rate, 157.3 TFLOP/s = 78.6 T lane-instructions/s (256 CUs x 4 SIMDs x 32 lanes x
+        # 2.4 GHz: a wave instruction per 2 clocks per SIMD).  sdkde_peaks measures 62 (v_fma_f32) to 72 (v_add_f32)
+        # T lane-instructions/s for independent plain instructions from two or more waves, 19.4 for v_exp_f32, and
+        # 20.3 clocks for one exp and four FMAs issued in groups (16 at the published rates): the mix ceiling below.
+        slots = (3 * d + 1 + 4) * float(n) * n
+        peak = 256 * 4 * 32 * 2.4e9 / 1e12
         ach = slots / (score_avg_ms * 1e-3) / 1e12
         out["roofline"] = {"bound": "alu", "achieved": ach, "peak": peak, "unit": "T lane-slots/s", "frac": ach / peak,
                            "traffic": None, "kernel": "pair_thin_kernel (score)", "launch_ms": score_avg_ms,
-                           "slots_per_pair": 3 * d + 3}
+                           "slots_per_pair": 3 * d + 5,
+                           "frac_ceiling_of_instruction_mix": (8.0 + 2.0 * (3 * d + 1)) / (8.1 + 3.05 * (3 * d + 1))}
     if not P.sdkde_describe_plan(n, m, d, 2)["thin"]:
         # the second kernel of the step, for completeness: 2d flops per pair (the cross term only); per tile 4 d/16
         # MFMAs against the same VALU work as the score kernel

@@ -1,5 +1,6 @@
 // sdkde_peaks: measures, on the GPU it runs on, the instruction rates the SD-KDE pair kernels are
-// bounded by: fp32 MFMA (16x16x4 and 32x32x2), v_exp_f32, v_fma_f32, and how fp32 MFMA and VALU
+// bounded by: fp32 MFMA (16x16x4 and 32x32x2), the issue rates of v_fma_f32 / v_add_f32 / v_exp_f32 and of
+// their mix in different orders, how fp32 MFMA and VALU
 // work share a SIMD (NM MFMAs per iteration with NE exps and NA adds, all mutually independent), and
 // the same for the fp16 MFMAs of the lower-precision input modes.
 // Cycle figures assume the nominal 2.4 GHz engine clock.
@@ -46,20 +47,6 @@ __global__ __launch_bounds__(kBlock) void mfma32_kernel(float* out, int iters, f
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-template <bool EXP>
-__global__ __launch_bounds__(kBlock) void valu_kernel(float* out, int iters, float a, float b)
-{
-    float v[8];
-    for (int c = 0; c < 8; ++c) v[c] = -0.001f * (threadIdx.x + c);
-    for (int i = 0; i < iters; ++i) {
-#pragma unroll
-        for (int c = 0; c < 8; ++c) v[c] = EXP ? __builtin_amdgcn_exp2f(v[c]) : fmaf(v[c], a, b);
-    }
-    float s = 0;
-    for (int c = 0; c < 8; ++c) s += v[c];
-    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
-}
-
 // NM MFMAs, NE exps, NA adds per iteration; the VALU work is dealt evenly over the MFMA slots
 // (SPREAD) or issued as one clump after all MFMAs.
 template <int NM, int NE, int NA, bool SPREAD>
@@ -97,6 +84,60 @@ __global__ __launch_bounds__(kBlock) void mix_kernel(float* out, int iters, floa
     float r = 0;
     for (int c = 0; c < 4; ++c) r += acc[c].x + acc[c].y + acc[c].z + acc[c].w;
     for (int c = 0; c < 8; ++c) r += e[c] + s[c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
+// Sustained issue rate of one VALU instruction (WHAT 0: v_fma_f32, 1: v_add_f32, 2: v_exp_f32): 128 independent
+// instructions per iteration over 16 registers, pinned with volatile asm so that none is merged or reordered.
+#define SDKDE_FMA(k) asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(s[(k) % 16]) : "v"(a), "v"(b))
+#define SDKDE_ADD(k) asm volatile("v_add_f32 %0, %0, %1" : "+v"(s[(k) % 16]) : "v"(a))
+#define SDKDE_EXP(k) asm volatile("v_exp_f32 %0, %0" : "+v"(e[(k) % 16]))
+#define SDKDE_R16(OP) OP(0); OP(1); OP(2); OP(3); OP(4); OP(5); OP(6); OP(7); OP(8); OP(9); OP(10); OP(11); OP(12); OP(13); OP(14); OP(15);
+#define SDKDE_R128(OP) SDKDE_R16(OP) SDKDE_R16(OP) SDKDE_R16(OP) SDKDE_R16(OP) SDKDE_R16(OP) SDKDE_R16(OP) SDKDE_R16(OP) SDKDE_R16(OP)
+template <int WHAT>
+__global__ __launch_bounds__(kBlock) void issue_kernel(float* out, int iters, float a, float b)
+{
+    float s[16], e[16];
+    for (int c = 0; c < 16; ++c) s[c] = e[c] = -0.001f * (threadIdx.x + c);
+    for (int i = 0; i < iters; ++i) {
+        if (WHAT == 0) { SDKDE_R128(SDKDE_FMA) }
+        if (WHAT == 1) { SDKDE_R128(SDKDE_ADD) }
+        if (WHAT == 2) { SDKDE_R128(SDKDE_EXP) }
+    }
+    float r = 0;
+    for (int c = 0; c < 16; ++c) r += s[c] + e[c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
+// The thin path's mix, 16 v_exp_f32 and 64 independent v_fma_f32 per iteration, in three orders:
+// ORDER 0: (exp, 4 fma) x 16; 1: 16 exp, then 64 fma; 2: (4 exp, 16 fma) x 4.
+#define SDKDE_F4(k) SDKDE_FMA(4 * (k)); SDKDE_FMA(4 * (k) + 1); SDKDE_FMA(4 * (k) + 2); SDKDE_FMA(4 * (k) + 3);
+#define SDKDE_E4(k) SDKDE_EXP(4 * (k)); SDKDE_EXP(4 * (k) + 1); SDKDE_EXP(4 * (k) + 2); SDKDE_EXP(4 * (k) + 3);
+template <int ORDER>
+__global__ __launch_bounds__(kBlock) void exp_order_kernel(float* out, int iters, float a, float b)
+{
+    float s[16], e[16];
+    for (int c = 0; c < 16; ++c) s[c] = e[c] = -0.001f * (threadIdx.x + c);
+    for (int i = 0; i < iters; ++i) {
+        if (ORDER == 0) {
+#define SDKDE_G(k) SDKDE_EXP(k); SDKDE_F4(k)
+            SDKDE_G(0) SDKDE_G(1) SDKDE_G(2) SDKDE_G(3) SDKDE_G(4) SDKDE_G(5) SDKDE_G(6) SDKDE_G(7)
+            SDKDE_G(8) SDKDE_G(9) SDKDE_G(10) SDKDE_G(11) SDKDE_G(12) SDKDE_G(13) SDKDE_G(14) SDKDE_G(15)
+#undef SDKDE_G
+        }
+        if (ORDER == 1) {
+            SDKDE_E4(0) SDKDE_E4(1) SDKDE_E4(2) SDKDE_E4(3)
+            SDKDE_F4(0) SDKDE_F4(1) SDKDE_F4(2) SDKDE_F4(3) SDKDE_F4(4) SDKDE_F4(5) SDKDE_F4(6) SDKDE_F4(7)
+            SDKDE_F4(8) SDKDE_F4(9) SDKDE_F4(10) SDKDE_F4(11) SDKDE_F4(12) SDKDE_F4(13) SDKDE_F4(14) SDKDE_F4(15)
+        }
+        if (ORDER == 2) {
+#define SDKDE_G(k) SDKDE_E4(k) SDKDE_F4(4 * (k)) SDKDE_F4(4 * (k) + 1) SDKDE_F4(4 * (k) + 2) SDKDE_F4(4 * (k) + 3)
+            SDKDE_G(0) SDKDE_G(1) SDKDE_G(2) SDKDE_G(3)
+#undef SDKDE_G
+        }
+    }
+    float r = 0;
+    for (int c = 0; c < 16; ++c) r += s[c] + e[c];
     out[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
@@ -174,6 +215,29 @@ void run_mix_f16(int waves_per_simd)
            K32 ? "16x16x32_f16" : "16x16x16_f16", NE, NA, waves_per_simd, clk);
 }
 
+template <int WHAT>
+void run_issue(const char* what)
+{
+    constexpr int iters = 4000;
+    for (int w : {1, 2, 4, 8}) {
+        const int blocks = kCUs * w;
+        float ms = time_ms([&] { hipLaunchKernelGGL(issue_kernel<WHAT>, dim3(blocks), dim3(kBlock), 0, 0, g_out, iters, 0.999f, 0.001f); });
+        printf("  %-10s %d waves/SIMD: %5.2f clk per wave instruction per SIMD, %6.2f T lane-ops/s\n", what, w,
+               ms * 1e-3 * kClockHz / iters / w / 128, 128.0 * iters * (double)blocks * kBlock / (ms * 1e-3) / 1e12);
+    }
+}
+
+template <int ORDER>
+void run_exp_order(const char* what)
+{
+    constexpr int iters = 10000;
+    for (int w : {4, 8}) {
+        const int blocks = kCUs * w;
+        float ms = time_ms([&] { hipLaunchKernelGGL(exp_order_kernel<ORDER>, dim3(blocks), dim3(kBlock), 0, 0, g_out, iters, 0.999f, 0.001f); });
+        printf("  %-22s %d waves/SIMD: %5.2f clk per (exp + 4 fma)\n", what, w, ms * 1e-3 * kClockHz / iters / w / 16);
+    }
+}
+
 }  // namespace
 
 int main()
@@ -184,7 +248,7 @@ int main()
         return 1;
     }
     printf("device: %s, %d CUs, %d kHz\n", prop.gcnArchName, prop.multiProcessorCount, prop.clockRate);
-    if (hipMalloc(&g_out, sizeof(float) * kBlock * kCUs * 4) != hipSuccess) return 1;
+    if (hipMalloc(&g_out, sizeof(float) * kBlock * kCUs * 8) != hipSuccess) return 1;
     if (hipEventCreate(&g_e0) != hipSuccess || hipEventCreate(&g_e1) != hipSuccess) return 1;
 
     printf("instruction peaks (4 waves per SIMD):\n");
@@ -194,10 +258,15 @@ int main()
     printf("  v_mfma_f32_16x16x4_f32 : %7.1f TFLOP/s\n", lanes * 4 * 32.0 / (ms * 1e-3) / 1e12);
     ms = time_ms([&] { hipLaunchKernelGGL(mfma32_kernel, dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 1.0f, 0.5f); });
     printf("  v_mfma_f32_32x32x2_f32 : %7.1f TFLOP/s\n", lanes * 2 * 64.0 / (ms * 1e-3) / 1e12);
-    ms = time_ms([&] { hipLaunchKernelGGL(valu_kernel<true>, dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 0.999f, 0.001f); });
-    printf("  v_exp_f32              : %7.2f T lane-ops/s\n", lanes * 8 / (ms * 1e-3) / 1e12);
-    ms = time_ms([&] { hipLaunchKernelGGL(valu_kernel<false>, dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 0.999f, 0.001f); });
-    printf("  v_fma_f32              : %7.2f T lane-ops/s\n", lanes * 8 / (ms * 1e-3) / 1e12);
+
+    printf("VALU issue, independent instructions (fp32 vector peak 157.3 TFLOP/s = 78.6 T FMA lane-ops/s = one wave instruction per 2 clk per SIMD):\n");
+    run_issue<0>("v_fma_f32");
+    run_issue<1>("v_add_f32");
+    run_issue<2>("v_exp_f32");
+    printf("16 v_exp_f32 and 64 v_fma_f32 per iteration, by order of issue (the thin path's mix):\n");
+    run_exp_order<0>("(exp, 4 fma) x 16");
+    run_exp_order<1>("16 exp, then 64 fma");
+    run_exp_order<2>("(4 exp, 16 fma) x 4");
 
     printf("fp32 MFMA and VALU on one SIMD (8 MFMAs = 256 clk if they overlapped perfectly):\n");
     for (int w : {1, 4}) {
