@@ -15,10 +15,10 @@
  *  - h is passed as double so that the derived constants are formed in double and rounded
  *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation) unless
  *    `flags` selects another input mode.
- *  - Accuracy domain of the matrix path (d >= 4): squared distances are formed as
+ *  - Accuracy domain of the matrix path (d >= 7, and the eval calls at d >= 4): squared distances are formed as
  *    |p|^2 + |x|^2 - 2 p.x on mean-centred coordinates, which loses about (R/h)^2 * 2^-24 in
  *    the exponent of phi (R = distance of a point from the sample mean).  The stated 1e-3
- *    tolerances hold while R/h stays below ~100; the thin path (d <= 3) uses direct
+ *    tolerances hold while R/h stays below ~100; the thin path (d <= 3, the score calls d <= 6) uses direct
  *    differences and has no such limit.  (Far outside that domain, R/h above ~1e18, the scaled
  *    coordinates overflow fp32 on either path and the outputs are NaN.)  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
  *    is kept: a point at which every phi_j is below the fp32 range (exponent under -126 ln 2)
@@ -56,7 +56,8 @@ enum {
     SDKDE_PREC_FP16X2 = 1,  /* each input split into two fp16 halves (hi + lo, ~22 mantissa bits) and
                                multiplied on the fp16 matrix units with fp32 accumulate; Phi X, exp and all
                                sums stay fp32.  A lower-precision-input mode: its error is reported
-                               separately.  Ignored (fp32 VALU) for d <= 3. */
+                               separately.  Ignored on the thin path (fp32 VALU: d <= 3, the score calls
+                               d <= 6). */
     SDKDE_PREC_FP16X2_ALL = 2, /* as FP16X2, and Phi X on the fp16 matrix units too: Phi is split in registers
                                into fp16 hi + lo (scaled by 2^14 to stay normal), X into hi + lo in the
                                prepared copy; fp32 accumulate, exp and the row sums D stay fp32.  The split
@@ -81,7 +82,7 @@ enum {
        mode, reported separately and against the same n^2 pair count.  Same results within the same tolerances,
        still without atomics and bit-reproducible, but more workspace (one partial [T | D] per row for each of
        up to 64 groups of sample blocks: about 4.6 GiB at n = 2^20, d = 16).  Takes effect where it pays: for
-       sdkde_score at the samples themselves and sdkde_fit_eval with 4 <= d <= 32, SDKDE_PREC_FP32 and enough samples to fill the chip with its work
+       sdkde_score at the samples themselves and sdkde_fit_eval with 7 <= d <= 32, SDKDE_PREC_FP32 and enough samples to fill the chip with its work
        items (n >= 32768 at d <= 16, n >= 16384 at d <= 32); ignored otherwise (sdkde_describe_plan tells). */
     SDKDE_FLAG_SYMMETRIC = 32,
     /* flags bit 6, sdkde_eval and sdkde_eval_laplace only (evaluating one fitted estimate at many batches of
@@ -171,7 +172,7 @@ int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, in
  * Introspection of the host-side plan (grid decomposition and workspace layout) that a call with these
  * sizes would use; touches no device.  call: 0 = sdkde_score at the samples, 1 = sdkde_score at m
  * separate points, 2 = sdkde_eval / sdkde_eval_laplace at m queries.  out (host, at least 20 entries):
- *   [0] thin path (d <= 3)   [1] padded dimension   [2] row tiles per wave (thin: rows per thread)
+ *   [0] thin path (0/1)      [1] padded dimension   [2] row tiles per wave (thin: rows per thread)
  *   [3] rows per workgroup   [4] row blocks         [5] splits of the sample axis
  *   [6] sample tiles per split   [7] sample tiles (of 16)   [8] padded sample rows   [9] padded point rows
  *   [10] workspace bytes     [11..17] byte offsets in the workspace of: prepared samples, their

@@ -22,7 +22,8 @@ constexpr float kPadNorm = -1.0e30f;   // "-|x|^2" of a padding sample: exp2 of 
 constexpr float kPadCoord = 1.0e18f;   // thin-d padding coordinate: squared distance ~1e36, exp2(-that) = 0
 constexpr int kMeanBlocks = 128;
 constexpr int kFlushTiles = 64;         // sample tiles between folds of the running sums (power of two)
-constexpr int kThinMaxD = 3;           // direct-difference path for d <= 3, MFMA path above
+constexpr int kThinMaxDScore = 6;      // direct-difference path for the score kinds up to this d, MFMA path above
+constexpr int kThinMaxDEval = 3;       // the same for the kinds without a numerator (eval, Laplace eval)
 
 // What a pair kernel accumulates.
 enum PairKind {

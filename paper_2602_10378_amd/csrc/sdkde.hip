@@ -179,10 +179,11 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
 {
     Plan p{};
     p.d = d;
-    // Direct differences on the VALU up to d = 3.  (Measured at n = 262144, m = 65536, fp32: at d = 4 / 5 the VALU
-    // form takes 25.7 / 30.4 ms for the score and 4.7 / 5.5 ms for eval, the matrix path with the shortened last
-    // block 26.1 / 29.9 ms and 2.8 / 3.7 ms.)
-    p.thin = d <= kThinMaxD;
+    // Direct differences on the VALU: up to d = 6 for the score kinds, up to d = 3 for eval.  Measured at
+    // n = 262144, m = 65536, fp32, VALU form against matrix form (with the shortened last block): score d = 4
+    // 19.8 / 26.2 ms, d = 5 22.9 / 29.9, d = 6 26.9 / 30.0, d = 7 30.6 / 30.0, d = 8 33.6 / 30.0; eval d = 4
+    // 3.7 / 2.8 ms, d = 5 4.2 / 3.7, d = 6 4.7 / 3.7.
+    p.thin = d <= (score ? kThinMaxDScore : kThinMaxDEval);
     p.dp = p.thin ? d : (int)round_up(d, 16);
     p.klast = p.thin ? 4 : (d - (p.dp - 16) + 3) / 4;
     p.n_pad = round_up(n, kRowPad);
@@ -193,7 +194,9 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
     // Candidate row-tile counts, largest (most operand reuse) first.
     int cand[5];
     int nc = 0;
-    if (p.thin) {
+    if (p.thin && d > kThinMaxDEval) {
+        cand[nc++] = 1;                 // built with one row per thread only
+    } else if (p.thin) {
         cand[nc++] = 4; cand[nc++] = 2; cand[nc++] = 1;
     } else {
         const int kb = p.dp / 16;
@@ -206,7 +209,8 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
     {
         // a forced value must be one the dispatch tables below instantiate
         const int kb = p.thin ? 0 : p.dp / 16;
-        const int widest = p.thin ? 4 : max_row_tiles(kb, score ? kScoreSelf : kEval, (int)effective_prec(flags, false, p.dp));
+        const int widest = p.thin ? (d > kThinMaxDEval ? 1 : 4)
+                                  : max_row_tiles(kb, score ? kScoreSelf : kEval, (int)effective_prec(flags, false, p.dp));
         const int narrowest = p.thin ? 1 : 2;
         if (forced_ni >= narrowest && forced_ni <= widest && (forced_ni & (forced_ni - 1)) == 0) {
             cand[0] = forced_ni;
@@ -416,6 +420,12 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
                                w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad,     \
                                laplace_c0, shift);                                                     \
     } while (0)
+// d = 4 .. 6: the kinds a score call runs (one row per thread)
+#define SDKDE_LAUNCH_THIN_SCORE(D_)                                                                    \
+    do {                                                                                               \
+        if constexpr (KIND == kScoreSelf || KIND == kScorePoints || KIND == kRowMax) SDKDE_LAUNCH_THIN(D_, 1); \
+        else return SDKDE_EUNSUPPORTED;                                                                \
+    } while (0)
 #define SDKDE_CASE_NI(KB_, NI_)                                            \
     case NI_:                                                              \
         if constexpr (NI_ <= max_row_tiles(KB_, KIND, PREC)) SDKDE_LAUNCH_MFMA(KB_, NI_); \
@@ -435,6 +445,9 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
             case 34: SDKDE_LAUNCH_THIN(3, 4); break;
             case 32: SDKDE_LAUNCH_THIN(3, 2); break;
             case 31: SDKDE_LAUNCH_THIN(3, 1); break;
+            case 41: SDKDE_LAUNCH_THIN_SCORE(4); break;
+            case 51: SDKDE_LAUNCH_THIN_SCORE(5); break;
+            case 61: SDKDE_LAUNCH_THIN_SCORE(6); break;
             default: return SDKDE_EUNSUPPORTED;
         }
     } else if (lds_staged(p.dp / 16, PREC) && (KIND == kEval || KIND == kEvalLaplace || KIND == kRowMax)) {
@@ -488,6 +501,7 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
         }
     }
 #undef SDKDE_CASE_NI
+#undef SDKDE_LAUNCH_THIN_SCORE
 #undef SDKDE_LAUNCH_THIN
 #undef SDKDE_LAUNCH_MFMA
 #undef SDKDE_LAUNCH_MFMA_K

@@ -16,7 +16,7 @@ def test_points_beyond_two_to_the_31_elements():
     import torch
     import paper_2602_10378_amd as P
     P.load()
-    n, d = 200, 4
+    n, d = 200, 7
     m = (1 << 27) + 12345                      # m_pad * 16 floats > 2^31
     print(f"large index: n={n} m={m} d={d}", flush=True)
     plan = P.sdkde_describe_plan(n, m, d, 1)
@@ -49,7 +49,7 @@ def test_samples_beyond_two_to_the_31_elements():
     import torch
     import paper_2602_10378_amd as P
     P.load()
-    n, d, m = (1 << 27) + 777, 4, 300           # n_pad * 16 floats > 2^31; 8.4 million sample tiles
+    n, d, m = (1 << 27) + 777, 7, 300           # n_pad * 16 floats > 2^31; 8.4 million sample tiles
     print(f"large index: n={n} m={m} d={d}", flush=True)
     plan = P.sdkde_describe_plan(n, m, d, 2)
     assert plan["n_pad"] * plan["dp"] > 2**31

@@ -37,7 +37,8 @@ def _mixture(n, m, d, seed):
 
 
 # sizes: several 16-sample tiles and row blocks plus ragged tails; d covers the thin path
-# (1-3), the MFMA path with zero-padded columns (5, 20, 33, 100) and exact multiples of 16.
+# (1-3, and 4-6 for the score), the MFMA path with zero-padded columns (4-5 eval, 7, 20, 33, 100) and
+# exact multiples of 16.
 CASES = [
     (4096, 1024, 16, 0),     # config C1
     (1000, 333, 16, 1),
@@ -47,6 +48,8 @@ CASES = [
     (1500, 300, 3, 4),
     (1200, 200, 4, 5),
     (1200, 200, 5, 6),
+    (1300, 210, 6, 13),
+    (1250, 190, 7, 14),
     (1100, 130, 20, 7),
     (1100, 130, 32, 8),
     (900, 100, 33, 9),
@@ -250,7 +253,7 @@ def test_eval_with_samples_prepared_by_the_previous_call(lib, n, d, flags):
 # work item, triangular items with more than one block) and the largest block size at small n.
 @pytest.mark.parametrize("n,d,seed,env", [
     (5000, 16, 0, {}), (5000, 16, 1, {"SDKDE_SYM_GROUPS": "3"}), (3000, 12, 2, {}), (7000, 20, 3, {}),
-    (6100, 32, 4, {"SDKDE_SYM_GROUPS": "4"}), (9000, 16, 5, {"SDKDE_SYM_RB": "2048"}), (4000, 5, 6, {"SDKDE_SYM_GROUPS": "1"}),
+    (6100, 32, 4, {"SDKDE_SYM_GROUPS": "4"}), (9000, 16, 5, {"SDKDE_SYM_RB": "2048"}), (4000, 7, 6, {"SDKDE_SYM_GROUPS": "1"}),
     (600, 16, 7, {}), (17, 8, 8, {}), (1, 16, 9, {})])
 def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
     P, torch = lib

@@ -15,7 +15,7 @@ FLAGS = [P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKD
 def _check(n, m, d, call, flags):
     p = P.sdkde_describe_plan(n, m, d, call, flags)
     rows = n if call == 0 else m
-    thin = d <= 3
+    thin = d <= (3 if call == 2 else 6)      # direct differences: eval up to d = 3, the score kinds up to d = 6
     assert p["thin"] == int(thin)
     assert p["dp"] == (d if thin else -(-d // 16) * 16)
     # rows: the grid's row blocks cover all evaluation rows and stay inside the padded point array
@@ -61,7 +61,7 @@ def _check(n, m, d, call, flags):
 
 def _check_symmetric(p, n, d, call, flags):
     """The symmetric mode's decomposition: whole blocks, non-empty groups, LDS within the CU's 160 KiB."""
-    wanted = bool(flags & P.SDKDE_FLAG_SYMMETRIC) and call == 0 and 4 <= d <= 32 and (flags & 15) == 0
+    wanted = bool(flags & P.SDKDE_FLAG_SYMMETRIC) and call == 0 and 7 <= d <= 32 and (flags & 15) == 0
     if not wanted:
         assert p["symmetric"] == 0
     elif p["symmetric"] == 0:        # declined: too few work items to fill the chip
