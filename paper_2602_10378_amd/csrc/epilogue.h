@@ -87,6 +87,80 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
     if (x_sd) x_sd[idx] = fmaf(half_h2, out, x[idx]);      // fused debiasing shift (sdkde_fit_eval)
 }
 
+// Matrix-path form of score_epilogue_kernel<kEpiPartsFew> (modes 0 and 2): a thread takes four consecutive
+// coordinates of one row, so the partial T is read with 16-byte loads (1 KiB per wave and slot instead of 256
+// bytes) by a quarter of the workgroups.  Same summation order, hence the same bits.  quad_io: the outputs (and x)
+// may be accessed 16 bytes at a time.
+// Grid: one workgroup per kBlock / kEpiPartsFew (row, four columns) pairs of the [m, dp] partials.
+__global__ __launch_bounds__(kBlock) void score_epilogue_quad_kernel(
+    const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
+    int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, int ps_split_half, float inv_ah2,
+    float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd, int quad_io)
+{
+    constexpr int PARTS = kEpiPartsFew, LANES = kBlock / PARTS;
+    __shared__ f32x4 red_t[PARTS][LANES];
+    __shared__ float red_d[PARTS][LANES];
+    const int lane = threadIdx.x % LANES, part = threadIdx.x / LANES;
+    const int quads = dp / 4;
+    const int64_t q = (int64_t)blockIdx.x * LANES + lane;
+    const bool active = q < m * quads;
+    const int64_t i = active ? q / quads : 0;
+    const int c0 = active ? (int)(q % quads) * 4 : 0;
+    f32x4 tacc = {0.0f, 0.0f, 0.0f, 0.0f};
+    float dacc = 0.0f;
+    if (active) {
+        for (int s = part; s < nsplit; s += PARTS) {
+            tacc += *reinterpret_cast<const f32x4*>(part_t + ((int64_t)s * m_pad + i) * dp + c0);
+            dacc += part_d[(int64_t)s * m_pad + i];
+        }
+    }
+    red_t[part][lane] = tacc;
+    red_d[part][lane] = dacc;
+    __syncthreads();
+    if (!active || part != 0 || c0 >= d) return;
+    f32x4 tsum = red_t[0][lane];
+    float dsum = red_d[0][lane];
+#pragma unroll
+    for (int k = 1; k < PARTS; ++k) {
+        tsum += red_t[k][lane];
+        dsum += red_d[k][lane];
+    }
+    f32x4 out;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int c = c0 + v;       // may run past d in the last quad: computed from padding, not stored
+        float pc;
+        if (ps_split_half) {
+            const _Float16* ph = reinterpret_cast<const _Float16*>(ps) + i * 2 * dp + (c / 16) * 32 + (c % 16);
+            pc = (float)ph[0] + (float)ph[16];
+        } else {
+            pc = ps[i * dp + ((c & ~15) | ((c & 3) << 2) | ((c >> 2) & 3))];      // fp32 layout of the prepared rows
+        }
+        float o = 0.0f;
+        if (mode == 2) o = fmaf(-pc, dsum, tsum[v]) / (dsum + 1.0f) * inv_ah2;
+        else if (dsum > 0.0f) o = (tsum[v] / dsum - pc) * inv_ah2;
+        out[v] = o;
+    }
+    const int64_t at = i * d + c0;
+    if (quad_io) {                  // d is a multiple of four and the caller's arrays are 16-byte aligned
+        if (score) *reinterpret_cast<f32x4*>(score + at) = out;
+        if (x_sd) {
+            const f32x4 xv = *reinterpret_cast<const f32x4*>(x + at);
+            f32x4 r;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) r[v] = fmaf(half_h2, out[v], xv[v]);
+            *reinterpret_cast<f32x4*>(x_sd + at) = r;
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            if (c0 + v >= d) break;
+            if (score) score[at + v] = out[v];
+            if (x_sd) x_sd[at + v] = fmaf(half_h2, out[v], x[at + v]);
+        }
+    }
+}
+
 // log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
 // signed != 0 (Laplace-corrected sum, which may be negative): density = sum * exp(lognorm) only.
 // shift (may be null): per-query base-2 exponent shift of the max-shifted mode.

@@ -722,9 +722,20 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     const int64_t total = m * (int64_t)d;
     const float inv_ah2 = (float)(1.0 / (a * h * h));
     const int nslots = p.sym_on ? p.sym_ngroups + 3 : p.nsplit + ((self && !p.thin) ? 1 : 0);
-    SDKDE_LAUNCH_EPILOGUE(score_epilogue_kernel, nslots, total, st, w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp,
-                          p.thin ? 1 : (self ? 2 : 0), effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0,
-                          inv_ah2, score_out, samples, (float)(0.5 * h * h), samples_sd_out);
+    const int ps_halves = effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0;
+    if (!p.thin && epilogue_parts(nslots, total) == kEpiPartsFew) {
+        const int64_t quads = m * (p.dp / 4);
+        constexpr int per_wg = kBlock / kEpiPartsFew;
+        const uintptr_t io = (uintptr_t)score_out | (uintptr_t)samples_sd_out | (samples_sd_out ? (uintptr_t)samples : 0);
+        const int quad_io = (d % 4 == 0 && (io & 15) == 0) ? 1 : 0;
+        hipLaunchKernelGGL(score_epilogue_quad_kernel, dim3((unsigned)((quads + per_wg - 1) / per_wg)), dim3(kBlock), 0, st,
+                           w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp, self ? 2 : 0, ps_halves, inv_ah2, score_out,
+                           samples, (float)(0.5 * h * h), samples_sd_out, quad_io);
+    } else {
+        SDKDE_LAUNCH_EPILOGUE(score_epilogue_kernel, nslots, total, st, w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d,
+                              p.dp, p.thin ? 1 : (self ? 2 : 0), ps_halves, inv_ah2, score_out, samples,
+                              (float)(0.5 * h * h), samples_sd_out);
+    }
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 

@@ -214,3 +214,29 @@ def test_concurrent_host_threads_with_their_own_streams(monkeypatch):
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads)
     assert not failures, failures
+
+
+def test_outputs_need_no_more_than_float_alignment():
+    """The C ABI takes plain float pointers: outputs (and the samples, for the shifted copy) that are only
+    4-byte aligned must give the bits of the 16-byte aligned call (the epilogue then stores scalars)."""
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    print("unaligned outputs", flush=True)
+    n, m, d = 3000, 100, 16
+    x, q, h = sdkde_inputs.make("C1", seed=3, n=n, m=m)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ws = P.make_workspace(n, m, d)
+    want_sd, _, want_log = P.sdkde_fit_eval(xd, qd, h, want="log", workspace=ws)
+    want_s = P.sdkde_score(xd, h, workspace=ws)
+    def shifted(t):
+        buf = torch.empty(t.numel() + 1, dtype=torch.float32, device="cuda")
+        view = buf[1:].view(t.shape)
+        assert view.data_ptr() % 16 == 4
+        return view
+    s_out, sd_out, x_off = shifted(want_s), shifted(want_sd), shifted(xd)
+    x_off.copy_(xd)
+    P.sdkde_score(x_off, h, out=s_out, workspace=ws)
+    assert torch.equal(s_out, want_s)
+    _, _, got_log = P.sdkde_fit_eval(x_off, qd, h, score_out=s_out, samples_sd_out=sd_out, want="log", workspace=ws)
+    assert torch.equal(sd_out, want_sd) and torch.equal(s_out, want_s) and torch.equal(got_log, want_log)
