@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
 # HBM bytes per launch of the score main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
 # read counter x2 and write counter x1 after calibration on the debias kernel): profiles/pipeline_<config>_*.txt
-SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4585981.3 * 2 + 557056.0) * 1024, "C4": (2390909.7 * 2 + 532480.0) * 1024}
+SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4586089.0 * 2 + 557056.0) * 1024, "C4": (2387123.2 * 2 + 532480.0) * 1024}
 # The paper's two timed shapes (one RTX A6000, TF32 dots), keyed by (config, n, m): seconds end to end.
 PAPER_SECONDS = {("C5", 1048576, 131072): 2.3,        # abstract / conclusion
                  ("C2", 32768, 4096): 2.11e-3}        # runtime table of the Results section (run with --config C2 --m 4096)
