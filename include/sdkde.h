@@ -25,6 +25,12 @@
  *    gets the documented all-underflow results instead of a shifted sum.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
  *    arguments give bit-identical outputs.
+ *  - Stream capture: the calls only launch kernels (no allocation, no memset, no host
+ *    synchronisation), so a sequence of them can be captured into a HIP graph.  One
+ *    exception: the first SDKDE_FLAG_SYMMETRIC score on a device raises that kernel's dynamic
+ *    LDS limit (a function attribute, set once per device and kernel), so make one such call
+ *    outside capture first.  The optional instrumentation records events and must stay off
+ *    during capture.
  *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
  *    are unspecified.  Two calls that share a workspace must be ordered on one stream.
  *  - Host threads: calls keep no state between them (the optional instrumentation below aside), so
