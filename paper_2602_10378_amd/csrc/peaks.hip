@@ -141,6 +141,37 @@ __global__ __launch_bounds__(kBlock) void exp_order_kernel(float* out, int iters
     out[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
+// Two waves per SIMD, 8 MFMAs then 4 exps and 8 adds as one clump: either two workgroups of 256 threads per compute
+// unit (the waves of a SIMD drift freely) or one of 512 whose barrier brings the two waves of every SIMD to their
+// VALU clumps together (BARRIER).
+template <int BLOCK, bool BARRIER>
+__global__ __launch_bounds__(BLOCK) void mix_aligned_kernel(float* out, int iters, float a, float b)
+{
+    f32x4 acc[4];
+    float e[8], s[8];
+    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0, 0, 0, 0};
+    for (int c = 0; c < 8; ++c) {
+        e[c] = -0.001f * (threadIdx.x + c);
+        s[c] = c;
+    }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[k % 4], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (BARRIER) __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(e[q]);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s[q] = s[q] + a;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float r = 0;
+    for (int c = 0; c < 4; ++c) r += acc[c].x + acc[c].y + acc[c].z + acc[c].w;
+    for (int c = 0; c < 8; ++c) r += e[c] + s[c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
 // fp16 MFMAs: K32 ? v_mfma_f32_16x16x32_f16 : v_mfma_f32_16x16x16_f16; NM of them, then NE exps and NA adds as one clump.
 template <bool K32, int NM, int NE, int NA>
 __global__ __launch_bounds__(kBlock) void mix_f16_kernel(float* out, int iters, float a, float b)
@@ -238,6 +269,15 @@ void run_exp_order(const char* what)
     }
 }
 
+template <int BLOCK, bool BARRIER>
+void run_mix_aligned(const char* what)
+{
+    const int blocks = kCUs * 2 * kBlock / BLOCK;       // two waves per SIMD either way
+    float ms = time_ms([&] { hipLaunchKernelGGL((mix_aligned_kernel<BLOCK, BARRIER>), dim3(blocks), dim3(BLOCK), 0, 0, g_out, kIters, 1.0f, 0.5f); });
+    printf("  8 MFMA +  4 exp +  8 add, one clump, 2 waves/SIMD, %-40s: %6.1f clk per iteration per wave\n", what,
+           ms * 1e-3 * kClockHz / kIters / 2);
+}
+
 }  // namespace
 
 int main()
@@ -280,6 +320,11 @@ int main()
         run_mix<8, 4, 8, false>(w);
         run_mix<8, 8, 16, false>(w);
     }
+
+    printf("do the VALU clumps of the two waves of a SIMD get cheaper when they coincide?\n");
+    run_mix_aligned<256, false>("two 256-thread workgroups per CU");
+    run_mix_aligned<512, false>("one 512-thread workgroup");
+    run_mix_aligned<512, true>("one 512-thread workgroup, barrier before");
 
     printf("fp16 MFMA and VALU on one SIMD (the 16x16x16 and 16x16x32 forms take the same time per instruction):\n");
     for (int w : {2, 4}) {
