@@ -95,7 +95,7 @@ enum {
        queries): the workspace still holds what the previous sdkde_eval / sdkde_eval_laplace call on it prepared
        from the same samples, n, d, h and precision mode, and nothing else has used the workspace since: the
        column means and the prepared samples are reused and only the queries are prepared (m may differ from
-       call to call; at n = 2^20 this saves about 0.3 ms per call).  The samples are not read.  The workspace
+       call to call, the workspace being large enough for each m used; at n = 2^20 this saves about 0.3 ms per call).  The samples are not read.  The workspace
        keeps a record of what was prepared (kind of call, samples pointer, n, d, h, precision mode); a call whose
        arguments do not match that record returns SDKDE_OK like any other but writes NaN to every output, so a
        broken precondition cannot pass for a result.  (Samples changed in place behind the same pointer are not

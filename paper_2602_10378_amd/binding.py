@@ -100,11 +100,18 @@ def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PR
     return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
 
-def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PREC_FP16X2_ALL) -> torch.Tensor:
-    """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes (by default sized for
-    the precision mode with the largest footprint, so one buffer serves every precision mode; the symmetric
-    score needs its flag here)."""
-    need = max(sdkde_workspace_bytes(n, m, d, SDKDE_PREC_FP16X2_ALL), sdkde_workspace_bytes(n, m, d, flags))
+def workspace_bytes_any_precision(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) -> int:
+    """The largest of sdkde_workspace_bytes over the three precision modes with the other flags as given: the
+    grid decomposition, and with it the number of partial-sum slots, depends on the precision mode."""
+    other = flags & ~15
+    return max(sdkde_workspace_bytes(n, m, d, other | prec)
+               for prec in (SDKDE_PREC_FP32, SDKDE_PREC_FP16X2, SDKDE_PREC_FP16X2_ALL))
+
+
+def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PREC_FP32) -> torch.Tensor:
+    """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes in every precision mode
+    (the symmetric score needs its flag here; a buffer made with it also serves calls without it)."""
+    need = max(workspace_bytes_any_precision(n, m, d, flags), workspace_bytes_any_precision(n, m, d, flags & ~SDKDE_FLAG_SYMMETRIC))
     return torch.empty(need, dtype=torch.uint8, device=device)
 
 

@@ -240,3 +240,28 @@ def test_outputs_need_no_more_than_float_alignment():
     assert torch.equal(s_out, want_s)
     _, _, got_log = P.sdkde_fit_eval(x_off, qd, h, score_out=s_out, samples_sd_out=sd_out, want="log", workspace=ws)
     assert torch.equal(sd_out, want_sd) and torch.equal(s_out, want_s) and torch.equal(got_log, want_log)
+
+
+def test_default_workspace_serves_every_precision_mode():
+    """A buffer from make_workspace with no flags must be accepted by every call in every precision mode: the
+    number of partial-sum slots depends on the mode (at n = 100000 the fp32 plan takes more splits than the fp16
+    ones), so the buffer is sized for the largest."""
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    print("default workspace, all precision modes", flush=True)
+    n, m, d = 100000, 1000, 16
+    x, q, h = sdkde_inputs.make("C1", seed=5, n=n, m=m)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ws = P.make_workspace(n, m, d)
+    ref = None
+    for flags in (P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_FLAG_MAX_SHIFT):
+        s = P.sdkde_score(xd, h, workspace=ws, flags=flags)
+        sp = P.sdkde_score(xd, h, points=qd, workspace=ws, flags=flags)
+        _, logd = P.sdkde_eval(xd, qd, h, want="log", workspace=ws, flags=flags)
+        if ref is None:
+            ref = (s, sp, logd)
+        else:       # the modes agree far inside the tolerance they are each held to against the oracle
+            assert float((s - ref[0]).norm() / ref[0].norm()) < 1e-4
+            assert float((sp - ref[1]).norm() / ref[1].norm()) < 1e-4
+            assert float((logd - ref[2]).abs().max()) < 1e-3
