@@ -106,7 +106,11 @@ enum {
 /*
  * Bytes of workspace sufficient for each of: sdkde_score at the n samples themselves,
  * sdkde_score at m separate points, and sdkde_eval at m queries, all with n samples of
- * dimension d.  One block of this size serves the whole score -> debias -> eval pipeline.
+ * dimension d, called with these flags.  One block of this size serves the whole score ->
+ * debias -> eval pipeline.  The size depends on n, m, d and flags together (the grid
+ * decomposition, and with it the number of partial-sum slots, is chosen per shape and
+ * precision mode): a buffer shared by calls with different m or flags must have the largest of
+ * their sizes; a call whose buffer is too small returns SDKDE_EWORKSPACE and does nothing.
  * bytes: host pointer, written on success.
  */
 int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_t *bytes);
