@@ -101,3 +101,32 @@ def test_bench_refuses_more_than_one_gpu():
                               timeout=120)
         assert proc.returncode != 0
         assert "single-GPU" in (proc.stderr + proc.stdout)
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/sdkde.h must compile as C (no C++ or HIP in the interface) and a C program that takes the
+    address of every entry point must link against the built library (no GPU call is made)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    P.load()
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    header = open(os.path.join(root, "include", "sdkde.h")).read()
+    names = sorted(set(re.findall(r"\b(sdkde_[a-z_]+)\s*\(", header)))
+    lines = ['#include "sdkde.h"', "#include <stdio.h>", "typedef void (*fn_t)(void);", "int main(void)", "{",
+             f"    fn_t table[{len(names)}];", "    size_t bytes = 0;", "    int rc;"]
+    lines += [f"    table[{k}] = (fn_t)&{name};" for k, name in enumerate(names)]
+    lines += ["    rc = sdkde_workspace_bytes(4096, 1024, 16, SDKDE_PREC_FP32, &bytes);",
+              '    printf("%d %lu %s %d\\n", rc, (unsigned long)bytes, sdkde_status_string(rc), table[0] != 0);',
+              "    return rc;", "}", ""]
+    src = tmp_path / "use_sdkde.c"
+    src.write_text("\n".join(lines))
+    libdir = os.path.join(root, "paper_2602_10378_amd")
+    exe = tmp_path / "use_sdkde"
+    proc = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"), str(src),
+                           "-o", str(exe), "-L", libdir, "-lsdkde", f"-Wl,-rpath,{libdir}"], capture_output=True, text=True)
+    assert proc.returncode == 0, proc.stderr
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=60).stdout.split()
+    assert out[0] == "0" and int(out[1]) == P.sdkde_workspace_bytes(4096, 1024, 16) and out[2] == "ok" and out[3] == "1"
