@@ -101,16 +101,19 @@ def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PR
 
 
 def workspace_bytes_any_precision(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) -> int:
-    """The largest of sdkde_workspace_bytes over the three precision modes with the other flags as given: the
-    grid decomposition, and with it the number of partial-sum slots, depends on the precision mode."""
-    other = flags & ~15
-    return max(sdkde_workspace_bytes(n, m, d, other | prec)
-               for prec in (SDKDE_PREC_FP32, SDKDE_PREC_FP16X2, SDKDE_PREC_FP16X2_ALL))
+    """The largest of sdkde_workspace_bytes over the three precision modes, with and without the max-shifted
+    sums, the other flags as given: the grid decomposition (and with it the number of partial-sum slots) depends
+    on the precision mode, and the mode a score at separate points runs in depends on the shift."""
+    other = flags & ~(15 | SDKDE_FLAG_MAX_SHIFT)
+    return max(sdkde_workspace_bytes(n, m, d, other | prec | shift)
+               for prec in (SDKDE_PREC_FP32, SDKDE_PREC_FP16X2, SDKDE_PREC_FP16X2_ALL)
+               for shift in (0, SDKDE_FLAG_MAX_SHIFT))
 
 
 def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PREC_FP32) -> torch.Tensor:
-    """A device byte buffer large enough for sdkde_score / sdkde_eval at these sizes in every precision mode
-    (the symmetric score needs its flag here; a buffer made with it also serves calls without it)."""
+    """A device byte buffer large enough for every call at these sizes in every precision mode, with or without
+    SDKDE_FLAG_MAX_SHIFT (the symmetric score needs its flag here; a buffer made with it also serves calls
+    without it)."""
     need = max(workspace_bytes_any_precision(n, m, d, flags), workspace_bytes_any_precision(n, m, d, flags & ~SDKDE_FLAG_SYMMETRIC))
     return torch.empty(need, dtype=torch.uint8, device=device)
 

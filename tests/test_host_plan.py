@@ -125,13 +125,15 @@ def test_plan_fills_the_last_round_of_workgroups(n, m, d, call):
 @given(n=st.integers(1, 3_000_000), m=st.integers(1, 3_000_000), d=st.integers(1, 128),
        other=st.sampled_from([0, P.SDKDE_FLAG_MAX_SHIFT, P.SDKDE_FLAG_SYMMETRIC]))
 def test_one_workspace_serves_every_precision_mode(n, m, d, other):
-    """The decomposition (and the number of partial-sum slots) depends on the precision mode, so the buffer the
-    binding makes by default must cover the plan of every mode and call, with or without the symmetric flag."""
+    """The decomposition (and the number of partial-sum slots) depends on the precision mode, and the mode of a
+    score at separate points on the max-shift flag, so the buffer the binding makes by default must cover the plan
+    of every mode and call, with or without the shift and the symmetric flag."""
     size = max(P.workspace_bytes_any_precision(n, m, d, other), P.workspace_bytes_any_precision(n, m, d, other & ~P.SDKDE_FLAG_SYMMETRIC))
     for prec in (P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL):
-        for flags in (other | prec, (other & ~P.SDKDE_FLAG_SYMMETRIC) | prec):
-            for call in range(3):
-                assert P.sdkde_describe_plan(n, m, d, call, flags)["workspace_bytes"] <= size
+        for shift in (0, P.SDKDE_FLAG_MAX_SHIFT):
+            for flags in (other | prec | shift, (other & ~P.SDKDE_FLAG_SYMMETRIC) | prec | shift):
+                for call in range(3):
+                    assert P.sdkde_describe_plan(n, m, d, call, flags)["workspace_bytes"] <= size
 
 
 def test_describe_plan_rejects_bad_arguments():
