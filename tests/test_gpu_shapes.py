@@ -265,3 +265,37 @@ def test_default_workspace_serves_every_precision_mode():
             assert float((s - ref[0]).norm() / ref[0].norm()) < 1e-4
             assert float((sp - ref[1]).norm() / ref[1].norm()) < 1e-4
             assert float((logd - ref[2]).abs().max()) < 1e-3
+
+
+def test_every_call_and_flag_accepts_the_default_workspace():
+    """Seeded random shapes: a buffer from make_workspace (with the symmetric flag where that mode is asked for)
+    is accepted by every entry point under every combination of flags, and the outputs are finite where they
+    must be (no comparison with the oracle here: the parity tests do that)."""
+    import random
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    rng = random.Random(7)
+    for case in range(16):
+        d = rng.choice([1, 3, 4, 6, 7, 8, 16, 17, 32, 48, 64, 96, 128])
+        n = rng.choice([rng.randint(1, 3000), rng.randint(3000, 60000)])
+        m = rng.choice([rng.randint(1, 300), rng.randint(300, 20000)])
+        print(f"default workspace case {case}: n={n} m={m} d={d}", flush=True)
+        gen = torch.Generator(device="cuda").manual_seed(case)
+        x = torch.randn(n, d, device="cuda", generator=gen)
+        q = torch.randn(m, d, device="cuda", generator=gen)
+        h = 1.0 + 0.1 * d**0.5
+        plain = P.make_workspace(n, m, d)
+        symmetric = P.make_workspace(n, m, d, flags=P.SDKDE_FLAG_SYMMETRIC)
+        for flags in (0, 1, 2, 16, 17, 18, 32, 48):
+            ws = symmetric if flags & P.SDKDE_FLAG_SYMMETRIC else plain
+            s = P.sdkde_score(x, h, workspace=ws, flags=flags)
+            sp = P.sdkde_score(x, h, points=q, workspace=ws, flags=flags)
+            _, logd = P.sdkde_eval(x, q, h, want="both", workspace=ws, flags=flags)
+            lap = P.sdkde_eval_laplace(x, q, h, workspace=ws, flags=flags)
+            x_sd, _, logd2 = P.sdkde_fit_eval(x, q, h, want="both", workspace=ws, flags=flags)
+            for t in (s, sp, lap, x_sd):
+                assert bool(torch.isfinite(t).all()), (case, flags)
+            assert not bool(torch.isnan(logd).any()) and not bool(torch.isnan(logd2).any()), (case, flags)
+            if flags & P.SDKDE_FLAG_MAX_SHIFT:
+                assert bool(torch.isfinite(logd).all()), (case, flags)
