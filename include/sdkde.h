@@ -24,7 +24,8 @@
  *    is kept: a point at which every phi_j is below the fp32 range (exponent under -126 ln 2)
  *    gets the documented all-underflow results instead of a shifted sum.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
- *    arguments give bit-identical outputs.
+ *    arguments (and a workspace of at least sdkde_workspace_bytes, or of the same size) give
+ *    bit-identical outputs.
  *  - Stream capture: the calls only launch kernels (no allocation, no memset, no host
  *    synchronisation), so a sequence of them can be captured into a HIP graph.  One
  *    exception: the first SDKDE_FLAG_SYMMETRIC score on a device raises that kernel's dynamic
@@ -109,8 +110,12 @@ enum {
  * dimension d, called with these flags.  One block of this size serves the whole score ->
  * debias -> eval pipeline.  The size depends on n, m, d and flags together (the grid
  * decomposition, and with it the number of partial-sum slots, is chosen per shape and
- * precision mode): a buffer shared by calls with different m or flags must have the largest of
- * their sizes; a call whose buffer is too small returns SDKDE_EWORKSPACE and does nothing.
+ * precision mode).  A call given less than its own size (a buffer made for another m, say)
+ * falls back to fewer splits of the samples - the same results to rounding, in a different but
+ * equally fixed summation order, slower when there are few points - and returns
+ * SDKDE_EWORKSPACE, doing nothing, only if its smallest decomposition does not fit either (a
+ * buffer made for m points always serves fewer points with the same n, d and flags).  The
+ * symmetric mode has one decomposition only and is refused without its full size.
  * bytes: host pointer, written on success.
  */
 int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_t *bytes);

@@ -371,6 +371,21 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base, ui
 
 bool bad_bandwidth(double h) { return !(h > 0.0) || !isfinite(h); }
 
+// For a workspace smaller than the plan's own decomposition needs (a buffer sized for another m, say): halves the
+// splits, down to one group per XCD (a single split for tiny sample sets).  False when already there.  Fewer
+// splits mean fewer partial-sum slots; the call is then slower for few points but needs less memory.
+bool fewer_splits(Plan& p)
+{
+    const int least = p.ntiles >= 128 ? 8 : 1;
+    if (p.sym_on || p.nsplit <= least) return false;
+    int s = p.nsplit / 2;
+    if (least == 8) s = s / 8 * 8;
+    p.nsplit = s < least ? least : s;
+    p.tiles_per_split = (p.ntiles + p.nsplit - 1) / p.nsplit;
+    p.tiles_per_split += p.tiles_per_split & 1;
+    return true;
+}
+
 // Optional instrumentation: event pairs around the main pair kernel of each call.
 constexpr int kProfileSlots = 256;
 struct Profile {
@@ -695,7 +710,8 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
 
     Plan p = make_plan(n, m, d, true, flags);
     apply_symmetric(p, n, flags, self);
-    const Workspace w = layout(p, true, !self, workspace, flags);
+    Workspace w = layout(p, true, !self, workspace, flags);
+    while (w.bytes > workspace_bytes && fewer_splits(p)) w = layout(p, true, !self, workspace, flags);
     if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
 
@@ -750,8 +766,9 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if (!queries || (!density_out && !log_density_out)) return SDKDE_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
 
-    const Plan p = make_plan(n, m, d, false, flags);
-    const Workspace w = layout(p, false, true, workspace, flags);
+    Plan p = make_plan(n, m, d, false, flags);
+    Workspace w = layout(p, false, true, workspace, flags);
+    while (w.bytes > workspace_bytes && fewer_splits(p)) w = layout(p, false, true, workspace, flags);
     if (w.bytes > workspace_bytes) return SDKDE_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
 

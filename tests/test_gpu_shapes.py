@@ -299,3 +299,30 @@ def test_every_call_and_flag_accepts_the_default_workspace():
             assert not bool(torch.isnan(logd).any()) and not bool(torch.isnan(logd2).any()), (case, flags)
             if flags & P.SDKDE_FLAG_MAX_SHIFT:
                 assert bool(torch.isfinite(logd).all()), (case, flags)
+
+
+def test_a_workspace_made_for_more_points_serves_fewer():
+    """The decomposition is chosen per shape, and a smaller m can prefer more splits (more partial-sum slots) than
+    the m a buffer was made for; the call then falls back to fewer splits instead of failing, with the same
+    results to rounding."""
+    import torch
+    import paper_2602_10378_amd as P
+    P.load()
+    for n, m_made, m, d in ((72994, 73086, 54645, 16), (40000, 36000, 24000, 32)):
+        size = P.sdkde_workspace_bytes(n, m_made, d)
+        want_size = P.sdkde_describe_plan(n, m, d, 1)["workspace_bytes"]
+        print(f"shared workspace n={n} made for m={m_made} ({size} B), used with m={m} (prefers {want_size} B)", flush=True)
+        gen = torch.Generator(device="cuda").manual_seed(n)
+        x = torch.randn(n, d, device="cuda", generator=gen)
+        q = torch.randn(m, d, device="cuda", generator=gen)
+        h = 1.5
+        ws = torch.empty(size, dtype=torch.uint8, device="cuda")
+        got_s = P.sdkde_score(x, h, points=q, workspace=ws)
+        got_e = P.sdkde_eval(x, q, h, want="log", workspace=ws)[1]
+        ref_s = P.sdkde_score(x, h, points=q)
+        ref_e = P.sdkde_eval(x, q, h, want="log")[1]
+        assert float((got_s - ref_s).norm() / ref_s.norm()) < 1e-5
+        assert float((got_e - ref_e).abs().max()) < 1e-4
+        assert torch.equal(got_s, P.sdkde_score(x, h, points=q, workspace=ws))      # still deterministic
+    # the first shape is one where the preferred decomposition does not fit the shared buffer
+    assert P.sdkde_describe_plan(72994, 54645, 16, 1)["workspace_bytes"] > P.sdkde_workspace_bytes(72994, 73086, 16)
