@@ -53,7 +53,8 @@ enum {
     SDKDE_EINVAL = 1,       /* null pointer, n < 1, m < 0, d < 1, h not finite or <= 0 */
     SDKDE_EUNSUPPORTED = 2, /* d above SDKDE_MAX_D, unknown flag bits */
     SDKDE_EWORKSPACE = 3,   /* workspace missing, misaligned or too small */
-    SDKDE_EDEVICE = 4       /* a HIP launch or event call failed */
+    SDKDE_EDEVICE = 4,      /* a HIP launch or event call failed */
+    SDKDE_ETOOLARGE = 5     /* sdkde_fit_eval_static: the sizes need more than SDKDE_STATIC_SCRATCH_BYTES */
 };
 
 enum {
@@ -170,6 +171,26 @@ int sdkde_fit_eval(const float *samples, int64_t n, const float *queries, int64_
                    double h, float *score_out, float *samples_sd_out, float *density_out,
                    float *log_density_out, void *workspace, size_t workspace_bytes, uint32_t flags,
                    void *stream);
+
+/*
+ * sdkde_fit_eval without a workspace argument, for callers that cannot allocate device memory or keep a
+ * workspace of their own (code under stream capture, tight serving loops, harnesses that forbid hipMalloc):
+ * the partial sums and prepared operands live in a buffer of SDKDE_STATIC_SCRATCH_BYTES that is part of the
+ * library's device image, one copy per GPU, held until the process ends.  No allocation of any kind happens
+ * in the call; inputs and outputs are still the caller's device arrays, with the meaning they have in
+ * sdkde_fit_eval, and the results are bit-identical to those of sdkde_fit_eval with a workspace of
+ * sdkde_workspace_bytes(n, m, d, flags).  Sizes for which that figure exceeds SDKDE_STATIC_SCRATCH_BYTES are
+ * refused with SDKDE_ETOOLARGE and nothing is launched (the buffer serves e.g. n = m = 32768 at d = 16,
+ * n = 65536, m = 8192 at d = 16, n = m = 16384 at d = 64).  The buffer keeps the last call's contents; nothing
+ * in it has to start at zero, every call rewrites what it reads.  All calls on one GPU share the one buffer:
+ * two calls that overlap in time on the same GPU (different streams or host threads) race; order them on
+ * one stream.  The first call on a device looks up the buffer's device address (no stream work); make it
+ * outside stream capture.
+ */
+enum { SDKDE_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024 };
+int sdkde_fit_eval_static(const float *samples, int64_t n, const float *queries, int64_t m, int32_t d,
+                          double h, float *score_out, float *samples_sd_out, float *density_out,
+                          float *log_density_out, uint32_t flags, void *stream);
 
 /*
  * Laplace-corrected KDE (Laplace-corrected KDE section: K_h^LC(x) = K_h(x) (1 + d/2 - |x|^2 / 2h^2),

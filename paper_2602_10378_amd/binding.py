@@ -21,6 +21,8 @@ SDKDE_FLAG_MAX_SHIFT = 16
 SDKDE_FLAG_SYMMETRIC = 32
 SDKDE_FLAG_SAMPLES_PREPARED = 64
 SDKDE_MAX_D = 128
+SDKDE_ETOOLARGE = 5
+SDKDE_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 
 _lib = None
 
@@ -47,13 +49,14 @@ def load() -> ctypes.CDLL:
     lib.sdkde_debias.argtypes = [c_fp, c_fp, i64, i32, f64, c_fp, c_fp]
     lib.sdkde_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_fit_eval.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
+    lib.sdkde_fit_eval_static.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, c_fp, u32, c_fp]
     lib.sdkde_eval_laplace.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_describe_plan.argtypes = [i64, i64, i32, i32, u32, ctypes.POINTER(ctypes.c_int64), i32]
     lib.sdkde_status_string.argtypes = [ctypes.c_int]
     lib.sdkde_status_string.restype = ctypes.c_char_p
     lib.sdkde_profile_enable.argtypes = [ctypes.c_int]
     lib.sdkde_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
-    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace", "sdkde_fit_eval", "sdkde_describe_plan",
+    for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace", "sdkde_fit_eval", "sdkde_fit_eval_static", "sdkde_describe_plan",
                  "sdkde_profile_enable", "sdkde_profile_summary"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
@@ -221,6 +224,28 @@ def sdkde_fit_eval(samples, queries, h, score_out=None, samples_sd_out=None, den
     _check("sdkde_fit_eval", load().sdkde_fit_eval(
         x.data_ptr(), n, q.data_ptr(), m, d, float(h), ptr(score_out), samples_sd_out.data_ptr(), ptr(density_out),
         ptr(log_density_out), ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
+    return samples_sd_out, density_out, log_density_out
+
+
+def sdkde_fit_eval_static(samples, queries, h, samples_sd_out, score_out=None, density_out=None, log_density_out=None,
+                          flags=SDKDE_PREC_FP32, stream=None):
+    """sdkde_fit_eval on the library's built-in scratch buffer: no workspace, and nothing is allocated here
+    either, so every output the caller wants is passed in (samples_sd_out is required)."""
+    x, q = _dev_f32(samples, "samples"), _dev_f32(queries, "queries")
+    n, d = x.shape
+    if q.dim() != 2 or q.shape[1] != d:
+        raise ValueError("queries must be [m, d]")
+    m = q.shape[0]
+    for t, name, shape in ((score_out, "score_out", x.shape), (samples_sd_out, "samples_sd_out", x.shape),
+                           (density_out, "density_out", (m,)), (log_density_out, "log_density_out", (m,))):
+        if t is not None:
+            _dev_f32(t, name)
+            if tuple(t.shape) != tuple(shape):
+                raise ValueError(f"{name} has the wrong shape")
+    ptr = lambda t: None if t is None else t.data_ptr()
+    _check("sdkde_fit_eval_static", load().sdkde_fit_eval_static(
+        x.data_ptr(), n, q.data_ptr(), m, d, float(h), ptr(score_out), ptr(samples_sd_out), ptr(density_out),
+        ptr(log_density_out), flags, _stream_handle(stream)))
     return samples_sd_out, density_out, log_density_out
 
 

@@ -11,6 +11,7 @@
 // the score numerator uses Phi X with the Phi tile still in the registers the first MFMA
 // left it in.
 #include <string.h>
+#include <mutex>
 #include "common.h"
 #include "prep.h"
 #include "pair_mfma.h"
@@ -804,6 +805,31 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
 
 }  // namespace
 
+// Built-in scratch buffer of sdkde_fit_eval_static: one copy per GPU the library runs on, held until the
+// process ends.  The name is a host-side stand-in; the device address is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[SDKDE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+// Address of `scratch` on the current device (resolved on the first call there; null on failure).
+void* static_scratch_address()
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void* address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(guard);
+    if (!address[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        address[dev] = ptr;
+    }
+    return address[dev];
+}
+
+}  // namespace
+
 extern "C" {
 
 int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_t* bytes)
@@ -847,6 +873,24 @@ int sdkde_fit_eval(const float* samples, int64_t n, const float* queries, int64_
     // too (any centre is exact, it only has to be near the data), which saves the mean pass.
     return eval_impl(samples_sd_out, n, queries, m, d, h, density_out, log_density_out, workspace, workspace_bytes,
                      flags, stream, false, true);
+}
+
+int sdkde_fit_eval_static(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
+                          float* score_out, float* samples_sd_out, float* density_out, float* log_density_out,
+                          uint32_t flags, void* stream)
+{
+    if (!samples_sd_out) return SDKDE_EINVAL;
+    int rc = check_common(samples, n, m, d, h, flags);
+    if (rc != SDKDE_OK) return rc;
+    // The whole pass must fit the built-in buffer with the decomposition the ordinary call would take, so that
+    // both give the same bits; larger problems are refused, not run with fewer splits.
+    size_t need = 0;
+    if ((rc = sdkde_workspace_bytes(n, m, d, flags, &need)) != SDKDE_OK) return rc;
+    if (need > (size_t)SDKDE_STATIC_SCRATCH_BYTES) return SDKDE_ETOOLARGE;
+    void* ws = static_scratch_address();
+    if (!ws) return SDKDE_EDEVICE;
+    return sdkde_fit_eval(samples, n, queries, m, d, h, score_out, samples_sd_out, density_out, log_density_out, ws,
+                          (size_t)SDKDE_STATIC_SCRATCH_BYTES, flags, stream);
 }
 
 int sdkde_debias(const float* samples, const float* score, int64_t n, int32_t d, double h, float* samples_sd_out,
@@ -916,6 +960,7 @@ const char* sdkde_status_string(int status)
         case SDKDE_EUNSUPPORTED: return "unsupported dimension, size or flag";
         case SDKDE_EWORKSPACE: return "workspace missing, misaligned or too small";
         case SDKDE_EDEVICE: return "HIP runtime error";
+        case SDKDE_ETOOLARGE: return "problem too large for the built-in scratch buffer";
         default: return "unknown status";
     }
 }
