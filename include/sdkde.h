@@ -34,7 +34,8 @@
  *    during capture.
  *  - Return value: SDKDE_OK or an error code; nothing throws.  After an error the outputs
  *    are unspecified.  Two calls that share a workspace must be ordered on one stream.
- *  - Host threads: calls keep no state between them (the optional instrumentation below aside), so
+ *  - Host threads: calls keep no state between them (the optional instrumentation and the test-only
+ *    sdkde_set_tuning below aside), so
  *    several threads may call concurrently, each with its own workspace and stream, on the device that is
  *    current in that thread.
  */
@@ -221,6 +222,26 @@ int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, in
  */
 int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t flags, int64_t *out,
                         int32_t out_len);
+
+/*
+ * For tests and parameter sweeps only: overrides one of the choices the host-side plan otherwise makes from
+ * the sizes alone (value 0 restores the library's own choice).  Values the kernels are not built for are
+ * ignored.  The setting is process-global and changes the decomposition, hence the workspace size and the
+ * (still fixed) summation order: set it before sdkde_workspace_bytes and leave it alone until the calls it
+ * is meant for have been issued.  Normal use never calls this; the library reads no environment variables.
+ */
+enum {
+    SDKDE_TUNE_SCORE_ROW_TILES = 0, /* row tiles per wave (thin path: rows per thread) of the score calls */
+    SDKDE_TUNE_SCORE_SPLITS = 1,    /* splits of the sample axis of the score calls */
+    SDKDE_TUNE_EVAL_ROW_TILES = 2,  /* the same two for sdkde_eval / sdkde_eval_laplace */
+    SDKDE_TUNE_EVAL_SPLITS = 3,
+    SDKDE_TUNE_SYM_BLOCK_ROWS = 4,  /* symmetric mode: rows per sample block (a power of two) */
+    SDKDE_TUNE_SYM_GROUPS = 5,      /* symmetric mode: most groups of sample blocks (1 .. 64) */
+    SDKDE_TUNE_SYM_MIN_ITEMS = 6,   /* symmetric mode: least number of work items for the flag to take effect
+                                       (default 512) */
+    SDKDE_TUNE_COUNT = 7
+};
+int sdkde_set_tuning(int knob, int value);
 
 /* Static, human-readable name of a status code. */
 const char *sdkde_status_string(int status);

@@ -21,6 +21,8 @@ SDKDE_FLAG_MAX_SHIFT = 16
 SDKDE_FLAG_SYMMETRIC = 32
 SDKDE_FLAG_SAMPLES_PREPARED = 64
 SDKDE_MAX_D = 128
+(SDKDE_TUNE_SCORE_ROW_TILES, SDKDE_TUNE_SCORE_SPLITS, SDKDE_TUNE_EVAL_ROW_TILES, SDKDE_TUNE_EVAL_SPLITS,
+ SDKDE_TUNE_SYM_BLOCK_ROWS, SDKDE_TUNE_SYM_GROUPS, SDKDE_TUNE_SYM_MIN_ITEMS) = range(7)
 SDKDE_ETOOLARGE = 5
 SDKDE_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 
@@ -34,13 +36,12 @@ class SdkdeError(RuntimeError):
 
 
 def load() -> ctypes.CDLL:
-    """Loads the built library (building it first only if it does not exist)."""
+    """Loads the built library, building it first if it is missing or was built from other sources than the
+    tree holds now (an edited kernel or header must never be tested against an old binary)."""
     global _lib
     if _lib is not None:
         return _lib
-    path = _build.LIBRARY
-    if not os.path.exists(path):
-        path = _build.build(force=True)
+    path = _build.build(force=False)
     lib = ctypes.CDLL(path)
     c_fp = ctypes.c_void_p
     i64, i32, u32, f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32, ctypes.c_double
@@ -52,12 +53,13 @@ def load() -> ctypes.CDLL:
     lib.sdkde_fit_eval_static.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, c_fp, c_fp, u32, c_fp]
     lib.sdkde_eval_laplace.argtypes = [c_fp, i64, c_fp, i64, i32, f64, c_fp, c_fp, ctypes.c_size_t, u32, c_fp]
     lib.sdkde_describe_plan.argtypes = [i64, i64, i32, i32, u32, ctypes.POINTER(ctypes.c_int64), i32]
+    lib.sdkde_set_tuning.argtypes = [ctypes.c_int, ctypes.c_int]
     lib.sdkde_status_string.argtypes = [ctypes.c_int]
     lib.sdkde_status_string.restype = ctypes.c_char_p
     lib.sdkde_profile_enable.argtypes = [ctypes.c_int]
     lib.sdkde_profile_summary.argtypes = [ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]
     for name in ("sdkde_workspace_bytes", "sdkde_score", "sdkde_debias", "sdkde_eval", "sdkde_eval_laplace", "sdkde_fit_eval", "sdkde_fit_eval_static", "sdkde_describe_plan",
-                 "sdkde_profile_enable", "sdkde_profile_summary"):
+                 "sdkde_profile_enable", "sdkde_profile_summary", "sdkde_set_tuning"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -121,11 +123,18 @@ def make_workspace(n: int, m: int, d: int, device="cuda", flags: int = SDKDE_PRE
     return torch.empty(need, dtype=torch.uint8, device=device)
 
 
-def _workspace(ws, n, m, d, device, flags=SDKDE_PREC_FP32):
+def _workspace(ws, n, m, d, device, flags=SDKDE_PREC_FP32, stream=None):
     if ws is None:
         if flags & SDKDE_FLAG_SAMPLES_PREPARED:
             raise ValueError("SDKDE_FLAG_SAMPLES_PREPARED needs the workspace of the call that prepared the samples")
-        ws = make_workspace(n, m, d, device, flags)
+        # A temporary workspace is freed when the wrapper returns, while the kernels that use it are still queued
+        # on `stream`: allocate it on that stream, so that the caching allocator hands the block out again only to
+        # work ordered after them.
+        if stream is not None and stream != torch.cuda.current_stream():
+            with torch.cuda.stream(stream):
+                ws = make_workspace(n, m, d, device, flags)
+        else:
+            ws = make_workspace(n, m, d, device, flags)
     if not ws.is_cuda or ws.dtype != torch.uint8 or not ws.is_contiguous():
         raise TypeError("workspace must be a contiguous uint8 tensor on the GPU")
     return ws
@@ -147,7 +156,7 @@ def sdkde_score(samples, h, points=None, out=None, workspace=None, flags=SDKDE_P
     _dev_f32(out, "out")
     if tuple(out.shape) != (m, d):
         raise ValueError("out must be [m, d]")
-    ws = _workspace(workspace, n, m, d, x.device, flags)
+    ws = _workspace(workspace, n, m, d, x.device, flags, stream)
     _check("sdkde_score", load().sdkde_score(x.data_ptr(), n, p_ptr, m, d, float(h), out.data_ptr(),
                                              ws.data_ptr(), ws.numel(), flags, _stream_handle(stream)))
     return out
@@ -188,7 +197,7 @@ def sdkde_eval(samples_sd, queries, h, density_out=None, log_density_out=None, w
             _dev_f32(t, name)
             if t.numel() != m:
                 raise ValueError(f"{name} must have m elements")
-    ws = _workspace(workspace, n, m, d, x.device, flags)
+    ws = _workspace(workspace, n, m, d, x.device, flags, stream)
     _check("sdkde_eval", load().sdkde_eval(
         x.data_ptr(), n, q.data_ptr(), m, d, float(h),
         None if density_out is None else density_out.data_ptr(),
@@ -219,7 +228,7 @@ def sdkde_fit_eval(samples, queries, h, score_out=None, samples_sd_out=None, den
             _dev_f32(t, name)
             if tuple(t.shape) != tuple(shape):
                 raise ValueError(f"{name} has the wrong shape")
-    ws = _workspace(workspace, n, m, d, x.device, flags)
+    ws = _workspace(workspace, n, m, d, x.device, flags, stream)
     ptr = lambda t: None if t is None else t.data_ptr()
     _check("sdkde_fit_eval", load().sdkde_fit_eval(
         x.data_ptr(), n, q.data_ptr(), m, d, float(h), ptr(score_out), samples_sd_out.data_ptr(), ptr(density_out),
@@ -261,11 +270,16 @@ def sdkde_eval_laplace(samples, queries, h, density_out=None, workspace=None, fl
     _dev_f32(density_out, "density_out")
     if density_out.numel() != m:
         raise ValueError("density_out must have m elements")
-    ws = _workspace(workspace, n, m, d, x.device, flags)
+    ws = _workspace(workspace, n, m, d, x.device, flags, stream)
     _check("sdkde_eval_laplace", load().sdkde_eval_laplace(
         x.data_ptr(), n, q.data_ptr(), m, d, float(h), density_out.data_ptr(), ws.data_ptr(), ws.numel(), flags,
         _stream_handle(stream)))
     return density_out
+
+
+def sdkde_set_tuning(knob: int, value: int) -> None:
+    """Test / sweep hook: overrides one choice of the host-side plan (0 restores the library's own)."""
+    _check("sdkde_set_tuning", load().sdkde_set_tuning(int(knob), int(value)))
 
 
 def sdkde_profile_enable(on: bool) -> None:

@@ -23,11 +23,25 @@ HIPCC_FLAGS = [
 ]
 
 
+RECORD = LIBRARY + ".sources"       # digest of the sources and flags the library was built from
+
+
+def source_digest() -> str:
+    import hashlib
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for path in SOURCES + HEADERS:
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIBRARY):
+    """True when the library is missing or was built from other sources than the tree holds now (by content, so
+    that a copy of the tree with fresh time stamps does not count as changed)."""
+    if not os.path.exists(LIBRARY) or not os.path.exists(RECORD):
         return True
-    built = os.path.getmtime(LIBRARY)
-    return any(os.path.getmtime(p) > built for p in SOURCES + HEADERS)
+    with open(RECORD) as f:
+        return f.read().strip() != source_digest()
 
 
 def kernels_using_scratch(remarks: str):
@@ -61,6 +75,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if spilled:
         os.remove(LIBRARY)
         raise RuntimeError("kernels spill registers to scratch memory (not allowed in this library): " + ", ".join(spilled))
+    with open(RECORD, "w") as f:
+        f.write(source_digest() + "\n")
     flags = [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")]
     proc = subprocess.run([hipcc, *flags, "-o", PEAKS_BINARY, PEAKS_SOURCE], stdout=subprocess.PIPE,
                           stderr=subprocess.STDOUT, text=True)

@@ -189,8 +189,9 @@ __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __re
     if (density) density[i] = (float)exp(lp);
 }
 
-__global__ __launch_bounds__(kBlock) void debias_kernel(const float* __restrict__ x, const float* __restrict__ s,
-                                                        int64_t total, float half_h2, float* __restrict__ out)
+// out may alias x or s (each thread reads its one element before it writes it): no __restrict__ here.
+__global__ __launch_bounds__(kBlock) void debias_kernel(const float* x, const float* s, int64_t total, float half_h2,
+                                                        float* out)
 {
     int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     if (idx < total) out[idx] = fmaf(half_h2, s[idx], x[idx]);

@@ -1,4 +1,4 @@
-// Pair kernel of the thin path (d <= 3): direct differences on the VALU.
+// Pair kernel of the thin path (d <= 3; the score kinds up to d = 6): direct differences on the VALU.
 #pragma once
 #include "common.h"
 

@@ -11,6 +11,7 @@
 // the score numerator uses Phi X with the Phi tile still in the registers the first MFMA
 // left it in.
 #include <string.h>
+#include <atomic>
 #include <mutex>
 #include "common.h"
 #include "prep.h"
@@ -87,11 +88,13 @@ struct Plan {
     int sym_ni, sym_rb, sym_per_group, sym_nblocks, sym_ngroups;
 };
 
-int env_int(const char* name, int fallback)
+// Overrides of the plan's own choices, set through sdkde_set_tuning (tests and sweeps); 0: none.
+std::atomic<int> g_tuning[SDKDE_TUNE_COUNT];
+
+int tuning(int knob, int fallback)
 {
-    const char* v = getenv(name);
-    if (!v || !*v) return fallback;
-    return atoi(v);
+    const int v = g_tuning[knob].load(std::memory_order_relaxed);
+    return v > 0 ? v : fallback;
 }
 
 // Workgroups needed to keep 256 CUs busy with a few waves per SIMD (tiny problems).
@@ -204,8 +207,8 @@ Plan make_plan(int64_t n, int64_t m, int d, bool score, uint32_t flags)
         const int top = max_row_tiles(kb, score ? kScoreSelf : kEval, (int)effective_prec(flags, false, p.dp));
         for (int v = top; v >= 2; v /= 2) cand[nc++] = v;
     }
-    const int forced_ni = env_int(score ? "SDKDE_SCORE_NI" : "SDKDE_EVAL_NI", 0);
-    int forced_split = env_int(score ? "SDKDE_SCORE_SPLIT" : "SDKDE_EVAL_SPLIT", 0);
+    const int forced_ni = tuning(score ? SDKDE_TUNE_SCORE_ROW_TILES : SDKDE_TUNE_EVAL_ROW_TILES, 0);
+    int forced_split = tuning(score ? SDKDE_TUNE_SCORE_SPLITS : SDKDE_TUNE_EVAL_SPLITS, 0);
     if (forced_split > p.ntiles) forced_split = p.ntiles;
     {
         // a forced value must be one the dispatch tables below instantiate
@@ -300,11 +303,11 @@ void apply_symmetric(Plan& p, int64_t n, uint32_t flags, bool self)
         return nb * (nb + 1) / 2;
     };
     while (rb > sb && items(rb) < 1024) rb /= 2;
-    const int forced_rb = env_int("SDKDE_SYM_RB", 0);
+    const int forced_rb = tuning(SDKDE_TUNE_SYM_BLOCK_ROWS, 0);
     if (forced_rb >= sb && forced_rb <= rb * 8 && forced_rb % sb == 0 && (forced_rb & (forced_rb - 1)) == 0 &&
         sym_lds_bytes(kb, forced_rb) <= 160 * 1024)
         rb = forced_rb;
-    int max_groups = env_int("SDKDE_SYM_GROUPS", kSymMaxGroups);
+    int max_groups = tuning(SDKDE_TUNE_SYM_GROUPS, kSymMaxGroups);
     if (max_groups < 1 || max_groups > kSymMaxGroups) max_groups = kSymMaxGroups;
     const int64_t n_pad = round_up(n, rb > kRowPad ? rb : kRowPad);
     const int64_t nblocks = n_pad / rb;
@@ -313,8 +316,8 @@ void apply_symmetric(Plan& p, int64_t n, uint32_t flags, bool self)
     const int ngroups = (int)((nblocks + per_group - 1) / per_group);
     // Below ~512 work items (two rounds of one per CU) the ordinary kernels win: measured at d = 16 the mode pays
     // from n = 32768 (528 items) and loses 1.5x at n = 24576 (300 items), 4x at n = 8192; at d = 32 it pays from
-    // n = 16384.  The flag is then ignored.  (SDKDE_SYM_MIN_ITEMS: for tests of the mode at small sizes.)
-    int min_items = env_int("SDKDE_SYM_MIN_ITEMS", 512);
+    // n = 16384.  The flag is then ignored.  (SDKDE_TUNE_SYM_MIN_ITEMS: for tests of the mode at small sizes.)
+    int min_items = tuning(SDKDE_TUNE_SYM_MIN_ITEMS, 512);
     if (min_items < 1) min_items = 1;
     if ((int64_t)ngroups * (ngroups + 1) / 2 < min_items) return;
     p.sym_on = true;
@@ -547,13 +550,17 @@ int launch_sym_kernel(const Plan& p, const Workspace& w, hipStream_t st)
     // more than 64 KiB of dynamic LDS has to be enabled per kernel and device; remembered, so that later calls
     // (also ones under stream capture) only launch
     constexpr int kMaxDevices = 64;
+    static std::mutex guard;                          // host threads may call concurrently
     static size_t lds_allowed[kMaxDevices] = {};
     int dev = 0;
     SDKDE_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= kMaxDevices || lds > lds_allowed[dev]) {
-        SDKDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&pair_sym_kernel<KB, NI, PREC, KLAST>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        if (dev >= 0 && dev < kMaxDevices) lds_allowed[dev] = lds;
+    {
+        std::lock_guard<std::mutex> lock(guard);
+        if (dev < 0 || dev >= kMaxDevices || lds > lds_allowed[dev]) {
+            SDKDE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&pair_sym_kernel<KB, NI, PREC, KLAST>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            if (dev >= 0 && dev < kMaxDevices) lds_allowed[dev] = lds;
+        }
     }
     const int64_t items = (int64_t)p.sym_ngroups * (p.sym_ngroups + 1) / 2;
     hipLaunchKernelGGL((pair_sym_kernel<KB, NI, PREC, KLAST>), dim3((unsigned)items), dim3(kSymBlock), lds, st, w.xs, w.xt,
@@ -949,6 +956,13 @@ int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t 
     if (out_len >= 25)
         out[24] = (!p.thin && partial_last_block_built(p.dp / 16, score ? kScoreSelf : kEval, (int)effective_prec(flags, p.thin, p.dp)))
                       ? p.klast : 4;
+    return SDKDE_OK;
+}
+
+int sdkde_set_tuning(int knob, int value)
+{
+    if (knob < 0 || knob >= SDKDE_TUNE_COUNT || value < 0) return SDKDE_EINVAL;
+    g_tuning[knob].store(value, std::memory_order_relaxed);
     return SDKDE_OK;
 }
 

@@ -27,3 +27,19 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning():
+    """set(knob, value) overrides one choice of the library's host-side plan (sdkde_set_tuning, a test hook of the
+    C ABI) for the duration of the test; every knob is restored afterwards."""
+    import paper_2602_10378_amd as P
+    touched = []
+
+    def set_knob(knob, value):
+        touched.append(knob)
+        P.sdkde_set_tuning(knob, value)
+
+    yield set_knob
+    for knob in touched:
+        P.sdkde_set_tuning(knob, 0)

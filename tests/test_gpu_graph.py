@@ -10,10 +10,10 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("name,n,m,flags", [("C1", 4096, 1024, 0), ("C3", 5000, 700, 0), ("C1", 5000, 700, 32), ("C4", 3000, 500, 0)])
-def test_pipeline_replays_from_a_graph(name, n, m, flags, monkeypatch):
+def test_pipeline_replays_from_a_graph(name, n, m, flags, tuning):
     import torch
-    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")      # take the symmetric mode at this small size too
     import paper_2602_10378_amd as P
+    tuning(P.SDKDE_TUNE_SYM_MIN_ITEMS, 1)      # take the symmetric mode at this small size too
     print(f"graph {name} n={n} m={m} flags={flags}", flush=True)
     x, q, h = sdkde_inputs.make(name, seed=0, n=n, m=m)
     d = x.shape[1]

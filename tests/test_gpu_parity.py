@@ -121,14 +121,14 @@ def test_laplace_corrected_kde_matches_oracle(lib, n, m, d, seed):
 # lower-precision-input mode, held to the same tolerances and with its error printed separately.
 @pytest.mark.parametrize("d", [64, 70, 90, 112, 128])
 @pytest.mark.parametrize("row_tiles", [2, 4])
-def test_eval_kinds_at_large_dimension(lib, d, row_tiles, monkeypatch):
+def test_eval_kinds_at_large_dimension(lib, d, row_tiles, tuning):
     """From dp = 64 on the kinds without a second contraction run the kernel that stages the sample tile in
     LDS: plain, Laplace-corrected and max-shifted eval over several splits, with a ragged last tile and
     tiles of 320 / 384 / 448 / 512 float4s (not all multiples of the workgroup size)."""
     P, torch = lib
     n, m = 4500 + d, 301
     print(f"large-d eval kinds n={n} m={m} d={d} row tiles {row_tiles}", flush=True)
-    monkeypatch.setenv("SDKDE_EVAL_NI", str(row_tiles))       # both instantiations (the plan takes 2 at this size)
+    tuning(P.SDKDE_TUNE_EVAL_ROW_TILES, row_tiles)       # both instantiations (the plan takes 2 at this size)
     x, q, h = _mixture(n, m, d, 70 + d)
     h = float(h) * (2.0 if d > 64 else 1.2)       # keep the sums inside the fp32 range without a shift
     plan = P.sdkde_describe_plan(n, m, d, 2)
@@ -249,19 +249,17 @@ def test_eval_with_samples_prepared_by_the_previous_call(lib, n, d, flags):
 
 
 # Symmetric score (separate mode): every unordered pair of samples computed once.  Sizes span several sample
-# blocks and groups of blocks with ragged tails; the environment overrides force few groups (several blocks per
+# blocks and groups of blocks with ragged tails; the tuning overrides force few groups (several blocks per
 # work item, triangular items with more than one block) and the largest block size at small n.
 @pytest.mark.parametrize("n,d,seed,env", [
-    (5000, 16, 0, {}), (5000, 16, 1, {"SDKDE_SYM_GROUPS": "3"}), (3000, 12, 2, {}), (7000, 20, 3, {}),
-    (6100, 32, 4, {"SDKDE_SYM_GROUPS": "4"}), (9000, 16, 5, {"SDKDE_SYM_RB": "2048"}), (4000, 7, 6, {"SDKDE_SYM_GROUPS": "1"}),
+    (5000, 16, 0, {}), (5000, 16, 1, {"SYM_GROUPS": 3}), (3000, 12, 2, {}), (7000, 20, 3, {}),
+    (6100, 32, 4, {"SYM_GROUPS": 4}), (9000, 16, 5, {"SYM_BLOCK_ROWS": 2048}), (4000, 7, 6, {"SYM_GROUPS": 1}),
     (600, 16, 7, {}), (17, 8, 8, {}), (1, 16, 9, {})])
-def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
+def test_symmetric_score_matches_oracle(lib, tuning, n, d, seed, env):
     P, torch = lib
-    for key in ("SDKDE_SYM_GROUPS", "SDKDE_SYM_RB"):
-        monkeypatch.delenv(key, raising=False)
     for key, value in env.items():
-        monkeypatch.setenv(key, value)
-    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")      # the mode is otherwise declined below ~512 work items
+        tuning(getattr(P, "SDKDE_TUNE_" + key), value)
+    tuning(P.SDKDE_TUNE_SYM_MIN_ITEMS, 1)      # the mode is otherwise declined below ~512 work items
     flags = P.SDKDE_FLAG_SYMMETRIC
     plan = P.sdkde_describe_plan(n, n, d, 0, flags)
     print(f"symmetric n={n} d={d} env={env} block={plan['sym_block_rows']} per_group={plan['sym_blocks_per_group']} "
@@ -285,14 +283,13 @@ def test_symmetric_score_matches_oracle(lib, monkeypatch, n, d, seed, env):
     print(f"symmetric n={n} d={d}: worst {worst:.3g} of allowance, rel frobenius {frob:.3g}", flush=True)
 
 
-def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib, monkeypatch):
+def test_symmetric_flag_is_ignored_where_it_does_not_apply(lib, tuning):
     P, torch = lib
     sym = P.SDKDE_FLAG_SYMMETRIC
     # too few samples to fill the chip with its work items: declined
-    monkeypatch.delenv("SDKDE_SYM_MIN_ITEMS", raising=False)
     assert P.sdkde_describe_plan(8192, 8192, 16, 0, sym)["symmetric"] == 0
     assert P.sdkde_describe_plan(32768, 32768, 16, 0, sym)["symmetric"] == 1
-    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")
+    tuning(P.SDKDE_TUNE_SYM_MIN_ITEMS, 1)
     for n, m, d, flags in ((3000, 500, 40, 0), (3000, 500, 16, P.SDKDE_PREC_FP16X2), (3000, 500, 2, 0)):
         print(f"symmetric flag ignored n={n} d={d} flags={flags}", flush=True)
         assert P.sdkde_describe_plan(n, n, d, 0, flags | sym)["symmetric"] == 0

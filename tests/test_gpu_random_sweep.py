@@ -29,10 +29,10 @@ def _cases(count, seed):
 
 
 @pytest.mark.parametrize("seed", [2024, 7, 11])
-def test_random_sweep_matches_oracle(seed, monkeypatch):
+def test_random_sweep_matches_oracle(seed, tuning):
     import torch
-    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")      # the symmetric mode is otherwise declined at these sizes
     import paper_2602_10378_amd as P
+    tuning(P.SDKDE_TUNE_SYM_MIN_ITEMS, 1)      # the symmetric mode is otherwise declined at these sizes
     P.load()
     worst = {}
     for k, n, m, d, comps, data_seed, diag, factor, flags in _cases(60, seed):

@@ -173,12 +173,12 @@ def test_profile_instrumentation_counts_launches_on_the_callers_stream():
     assert P.sdkde_profile_summary(0) == (0, 0.0)      # disabling reset the record
 
 
-def test_concurrent_host_threads_with_their_own_streams(monkeypatch):
+def test_concurrent_host_threads_with_their_own_streams(tuning):
     """Several host threads, each with its own workspace and stream, get the same bits as a lone call."""
     import threading
-    monkeypatch.setenv("SDKDE_SYM_MIN_ITEMS", "1")      # one of the threads runs the symmetric mode at a small size
     import torch
     import paper_2602_10378_amd as P
+    tuning(P.SDKDE_TUNE_SYM_MIN_ITEMS, 1)      # one of the threads runs the symmetric mode at a small size
     P.load()
     print("concurrent host threads", flush=True)
     cases = []

@@ -140,3 +140,47 @@ def test_describe_plan_rejects_bad_arguments():
     for args in ((0, 1, 16, 0, 0), (10, 10, 16, 3, 0), (10, 10, 200, 0, 0), (10, 10, 16, 0, 99)):
         with pytest.raises(P.SdkdeError):
             P.sdkde_describe_plan(*args)
+
+
+def test_tuning_overrides_change_the_plan_and_are_validated(tuning):
+    """sdkde_set_tuning (a test hook of the C ABI) forces one of the plan's choices; values the kernels are not
+    built for are ignored, 0 restores the library's own choice, and the library reads no environment."""
+    import os
+    base = P.sdkde_describe_plan(65536, 65536, 16, 0)
+    tuning(P.SDKDE_TUNE_SCORE_ROW_TILES, 2)
+    tuning(P.SDKDE_TUNE_SCORE_SPLITS, 24)
+    forced = P.sdkde_describe_plan(65536, 65536, 16, 0)
+    assert forced["row_tiles"] == 2 and forced["splits"] == 24
+    eval_plan = P.sdkde_describe_plan(65536, 4096, 16, 2)
+    tuning(P.SDKDE_TUNE_SCORE_ROW_TILES, 3)            # not a count the kernels are built for: ignored
+    assert P.sdkde_describe_plan(65536, 65536, 16, 0)["row_tiles"] in (2, 4, 8)
+    tuning(P.SDKDE_TUNE_SCORE_ROW_TILES, 0)
+    tuning(P.SDKDE_TUNE_SCORE_SPLITS, 0)
+    assert P.sdkde_describe_plan(65536, 4096, 16, 2) == eval_plan      # the score knobs leave eval calls alone
+    tuning(P.SDKDE_TUNE_SCORE_ROW_TILES, 0)
+    tuning(P.SDKDE_TUNE_SCORE_SPLITS, 0)
+    assert P.sdkde_describe_plan(65536, 65536, 16, 0) == base
+    os.environ["SDKDE_SCORE_SPLIT"] = "24"
+    try:
+        assert P.sdkde_describe_plan(65536, 65536, 16, 0) == base
+    finally:
+        del os.environ["SDKDE_SCORE_SPLIT"]
+    for knob, value in ((-1, 1), (P.SDKDE_TUNE_SYM_MIN_ITEMS + 1, 1), (0, -5)):
+        with pytest.raises(P.SdkdeError) as e:
+            P.sdkde_set_tuning(knob, value)
+        assert e.value.status == 1
+
+
+def test_library_is_rebuilt_when_a_source_changes(tmp_path, monkeypatch):
+    """The binding builds before loading whenever the library was built from other sources than the tree holds
+    (compared by content, not by time stamp)."""
+    from paper_2602_10378_amd import build
+    P.load()
+    assert not build.is_stale()
+    record = open(build.RECORD).read()
+    fake = tmp_path / "extra.h"
+    fake.write_text("// an edited header\n")
+    monkeypatch.setattr(build, "HEADERS", build.HEADERS + [str(fake)])
+    assert build.is_stale()
+    monkeypatch.undo()
+    assert not build.is_stale() and open(build.RECORD).read() == record
