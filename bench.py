@@ -1,13 +1,19 @@
 """Benchmark of the SD-KDE hot path on one MI355X.
 
-A step is one pass of the whole path (score at all samples -> debias -> KDE at the queries)
-over one synthetic batch that is already resident in HBM.  Prints one JSON line.
+A step is one pass of the whole path (score at all samples -> debias -> KDE of the shifted samples at the
+queries) over one synthetic batch that is already resident in HBM.  Prints one JSON line: the headline
+numbers for --config (default C5, the shape the metric is quoted on), a `per_config` block with the other
+configs timed in the same process, the separately reported modes with their own bounds, and the CPU oracle
+timed on a bounded sample of the same workload, which also serves as the reference of the sampled parity check.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--no-cpu-baseline] [--no-other-modes]
+                  [--no-per-config]
 """
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -15,46 +21,196 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
-# HBM bytes per launch of the score main kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (KiB per dispatch,
-# read counter x2 and write counter x1 after calibration on the debias kernel): profiles/pipeline_<config>_*.txt
-SCORE_KERNEL_TRAFFIC_BYTES = {"C5": (4586089.0 * 2 + 557056.0) * 1024, "C4": (2387123.2 * 2 + 532480.0) * 1024}
 # The paper's two timed shapes (one RTX A6000, TF32 dots), keyed by (config, n, m): seconds end to end.
 PAPER_SECONDS = {("C5", 1048576, 131072): 2.3,        # abstract / conclusion
-                 ("C2", 32768, 4096): 2.11e-3}        # runtime table of the Results section (run with --config C2 --m 4096)
+                 ("C2", 32768, 4096): 2.11e-3}        # runtime table of the Results section (--config C2 --m 4096)
+MODE_FLAGS = {"fp32": 0, "fp16x2": 1, "fp16x2_all": 2, "symmetric": 32}
+MODE_NOTES = {
+    "fp16x2": "cross-term inputs split into fp16 hi+lo on the fp16 matrix units, fp32 accumulate; Phi X fp32",
+    "fp16x2_all": "both contractions on the fp16 matrix units (inputs and Phi split into fp16 hi+lo), fp32 accumulate, "
+                  "exp and row sums fp32",
+    "symmetric": "fp32 path; the score computes each unordered pair of samples once (phi_ij = phi_ji) and is still "
+                 "counted as n^2 pairs, as the paper counts them"}
 
 
-def cpu_baseline(x, q, h, budget_s=15.0):
-    """Times the double-precision oracle (as is) on a bounded sample of the same workload:
-    the first r score rows against all n samples plus the first r*m/n queries against all n
-    shifted samples, r sized from a short calibration so the whole leg takes ~budget_s."""
-    import numpy as np
+def traffic_from_profile(config, plan):
+    """HBM bytes per launch of the score main kernel as the committed rocprofv3 --pmc summary of this config
+    recorded them (FETCH_SIZE / WRITE_SIZE, calibrated on a plain streaming kernel), with the kernel's algorithmic
+    bytes beside them: the prepared samples read once plus one partial-sum slot written per split."""
+    files = sorted(glob.glob(os.path.join(ROOT, "profiles", f"pipeline_{config}_*.txt")))
+    if not files:
+        return None, None
+    text = open(files[0]).read()
+    m = re.search(r"^traffic_json (.*)$", text, flags=re.M)
+    if not m:
+        return None, None
+    rec = json.loads(m.group(1))
+    n_pad, m_pad, dp, slots = plan["n_pad"], plan["m_pad"], plan["dp"], plan["partial_slots"]
+    xt = plan["xt_scale"] * n_pad * dp if plan["off_xt"] >= 0 else 0
+    algorithmic = 4.0 * (n_pad * dp + xt + n_pad) + 4.0 * slots * m_pad * ((dp + 1) if plan["off_part_t"] >= 0 else 1)
+    detail = {"source": os.path.relpath(files[0], ROOT), "kernel": rec["kernel"], "read_bytes": rec["read_bytes"],
+              "written_bytes": rec["written_bytes"], "algorithmic_bytes_of_the_launch": algorithmic,
+              "ratio_to_algorithmic": rec["bytes"] / algorithmic,
+              "note": "re-reads of the streamed samples come from L2 misses per XCD (each XCD streams its share of the "
+                      "samples once per round of resident workgroups); HBM stays non-binding"}
+    return rec["bytes"], detail
+
+
+class Workload:
+    """One config resident on the GPU, with its outputs and a workspace that serves every mode."""
+
+    def __init__(self, P, torch, sdkde_inputs, name, seed, n=None, m=None):
+        self.P, self.torch, self.name = P, torch, name
+        self.x, self.q, self.h = sdkde_inputs.make(name, seed=seed, n=n, m=m)
+        self.n, self.d = self.x.shape
+        self.m = self.q.shape[0]
+        dev = torch.device("cuda:0")
+        self.xd, self.qd = torch.from_numpy(self.x).to(dev), torch.from_numpy(self.q).to(dev)
+        self.ws = P.make_workspace(self.n, self.m, self.d, device=dev, flags=P.SDKDE_FLAG_SYMMETRIC)
+        self.s = torch.empty_like(self.xd)
+        self.x_sd = torch.empty_like(self.xd)
+        self.dens = torch.empty(self.m, dtype=torch.float32, device=dev)
+        self.logd = torch.empty(self.m, dtype=torch.float32, device=dev)
+        self.pairs = float(self.n) * self.n + float(self.m) * self.n
+
+    def step(self, flags=0):
+        P = self.P
+        P.sdkde_score(self.xd, self.h, out=self.s, workspace=self.ws, flags=flags)
+        P.sdkde_debias(self.xd, self.s, self.h, out=self.x_sd)
+        P.sdkde_eval(self.x_sd, self.qd, self.h, density_out=self.dens, log_density_out=self.logd, workspace=self.ws,
+                     flags=flags)
+
+    def fused_step(self, flags=0):
+        self.P.sdkde_fit_eval(self.xd, self.qd, self.h, score_out=self.s, samples_sd_out=self.x_sd, density_out=self.dens,
+                              log_density_out=self.logd, workspace=self.ws, flags=flags)
+
+    def timed(self, fn, steps, warmup):
+        """(seconds per step by the host clock around synchronisations, sorted per-step ms from events, main-kernel
+        ms per launch of the score and of the eval call from the library's own events on the launch stream)."""
+        P, torch = self.P, self.torch
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        P.sdkde_profile_enable(True)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        t0 = time.perf_counter()
+        marks[0].record()
+        for k in range(steps):
+            fn()
+            marks[k + 1].record()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+        (ls, score_ms), (le, eval_ms) = P.sdkde_profile_summary(0), P.sdkde_profile_summary(1)
+        P.sdkde_profile_enable(False)
+        return dt / steps, per_step, score_ms / max(ls, 1), eval_ms / max(le, 1)
+
+    def rooflines(self, score_ms, eval_ms, mode="fp32"):
+        from paper_2602_10378_amd import cost_model as cm
+        P, n, m, d = self.P, self.n, self.m, self.d
+        flags = MODE_FLAGS[mode]
+        plan_s, plan_e = P.sdkde_describe_plan(n, n, d, 0, flags), P.sdkde_describe_plan(n, m, d, 2, flags)
+        eff = mode
+        if mode == "symmetric" and not plan_s["symmetric"]:
+            eff = "fp32"
+        if mode == "fp16x2_all" and plan_s["xt_scale"] != 2:
+            eff = "fp16x2"
+        out = {}
+        for key, stage, ms, plan, pairs in (("roofline", "score", score_ms, plan_s, float(n) * n),
+                                            ("roofline_eval_kernel", "eval", eval_ms, plan_e, float(m) * n)):
+            thin = bool(plan["thin"])
+            r = cm.roofline(stage, d, pairs, ms * 1e-3, "fp32" if (stage == "eval" and eff == "symmetric") else eff, thin)
+            r["launch_ms"] = ms
+            r["kernel"] = ("pair_thin_kernel" if thin else "pair_sym_kernel + in-block pass" if (eff == "symmetric" and stage == "score")
+                           else "pair_lds_kernel" if (stage == "eval" and plan["dp"] >= 64 and eff == "fp32") else "pair_mfma_kernel") + f" ({stage})"
+            r["ceiling"] = self.mix_ceiling(stage, eff, thin)
+            out[key] = r
+        return out, plan_s
+
+    def mix_ceiling(self, stage, mode, thin):
+        """Share of the bound's peak that this kernel's instruction mix can reach on gfx950, where fp32 MFMA and
+        vector work do not overlap on a SIMD: from the clocks sdkde_peaks measures (profiles/peaks_*.txt)."""
+        d = self.d
+        if thin:
+            plain = (3 * d + 1) if stage == "score" else (2 * d + 1)
+            return {"frac": (8.0 + 2.0 * plain) / (8.1 + 3.05 * plain),
+                    "basis": "one v_exp_f32 (8.1 clk, overlaps nothing) + plain instructions at the measured 3.05 clk next to "
+                             "exps, against 8 + 2 per plain instruction at the published rates"}
+        blocks = -(-d // 16)
+        if mode == "fp32":
+            mfma = 32.0 * (8 if stage == "score" else 4) * blocks
+            return {"frac": (mfma * d / (16.0 * blocks)) / (mfma + 4 * 8 + 8 * 4 + (13 if stage == "score" else 6)),
+                    "basis": "per 16x16 tile: the MFMAs at 32 clk each, then 4 v_exp_f32 (8 clk) + 8 v_add_f32 (4 clk) that "
+                             "cannot overlap them, + 6-13 clk of switching (measured: 333 clk for the d = 16 score mix)"}
+        if mode == "symmetric":
+            return {"frac": 384.0 / 531.0 if blocks == 1 else None,
+                    "basis": "per tile of unordered pairs at d = 16: 12 MFMAs (384 clk) of 531 clk: + exp, row and column sums, "
+                             "the transpose through LDS and the fold of T_J"}
+        if mode == "fp16x2_all" and stage == "score":
+            return {"frac": 64.0 / 147.0 if blocks == 1 else None,
+                    "basis": "per tile at d = 16: 4 fp16 MFMAs (64 clk at the 2.5 PFLOP/s peak) of the 147 clk sdkde_peaks "
+                             "measures for 4 MFMAs + 4 exp + 16 plain instructions at two waves per SIMD"}
+        return {"frac": None, "basis": "mix not measured on its own"}
+
+    def run(self, steps, warmup, fn=None, mode="fp32"):
+        flags = MODE_FLAGS[mode]
+        sec, per_step, score_ms, eval_ms = self.timed(fn or (lambda: self.step(flags)), steps, warmup)
+        roofs, plan = self.rooflines(score_ms, eval_ms, mode)
+        out = {"ms_per_step": sec * 1e3, "value": self.pairs / sec, "unit": "pairs/s", "steps": steps,
+               "ms_per_step_min": per_step[0], "ms_per_step_median": per_step[len(per_step) // 2],
+               "stages_ms": {"score_main_kernel": score_ms, "eval_main_kernel": eval_ms,
+                             "everything_else": sec * 1e3 - score_ms - eval_ms}}
+        out.update(roofs)
+        return out, plan
+
+
+def oracle_sample(w, budget_s=15.0):
+    """The CPU-baseline leg: the double-precision oracle (as is) timed on a bounded sample of the same workload,
+    score rows and queries chosen as the parity tests choose them (random rows plus the rows at tile, row-block
+    and split boundaries), each against ALL n samples.  The eval leg evaluates the KDE of the unshifted samples
+    (the oracle cannot produce all n shifted samples at this size; the cost per pair is the same).  Returns the
+    baseline record and the reference values for the sampled parity checks."""
     import oracle
-    n, d = x.shape
-    m = q.shape[0]
+    import sdkde_inputs
+    n, m = w.n, w.m
     cal_rows, rate = 16, 0.0
     while True:                      # calibrate on a run long enough to amortise thread start-up
         cal_rows = min(n, cal_rows * 4)
         t0 = time.perf_counter()
-        oracle.score(x, h, points=x[:cal_rows])
+        oracle.score(w.x, w.h, points=w.x[:cal_rows])
         cal = time.perf_counter() - t0
         rate = cal_rows * n / max(cal, 1e-9)
         if cal >= 0.5 or cal_rows == n:
             break
-    rows = int(min(n, max(cal_rows, budget_s * rate / (n * (1.0 + m / n)))))
-    qrows = int(min(m, max(1, round(rows * m / n))))
+    want_rows = int(min(n, max(cal_rows, budget_s * rate / (n * (1.0 + m / n)))))
+    rows = sdkde_inputs.sample_rows(n, max(want_rows - 48, 16), seed=0)
+    qrows = sdkde_inputs.sample_rows(m, max(int(round(len(rows) * m / n)) - 48, 16), seed=1)
     t0 = time.perf_counter()
-    s_rows = oracle.score(x, h, points=x[:rows])
-    # eval leg: the shifted samples are an input here; any point set of the same shape costs
-    # the same, so the unshifted samples stand in for them in the timing
-    oracle.eval_log_density(x, q[:qrows], h)
+    s_ref = oracle.score(w.x, w.h, points=w.x[rows])
+    logp_ref = oracle.eval_log_density(w.x, w.q[qrows], w.h)
     dt = time.perf_counter() - t0
-    pairs = float(rows) * n + float(qrows) * n
-    return {
-        "value": pairs / dt, "unit": "pairs/s", "cores": oracle.threads(), "kind": "oracle",
-        "sample": f"first {rows} of {n} score rows + first {qrows} of {m} queries, each against all {n} samples "
-                  f"({pairs:.3g} pairs in {dt:.1f} s, fp64)",
-    }, s_rows
+    pairs = float(len(rows)) * n + float(len(qrows)) * n
+    base = {"value": pairs / dt, "unit": "pairs/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"{len(rows)} of {n} score rows + {len(qrows)} of {m} queries (random + tile/split-boundary rows), "
+                      f"each against all {n} samples ({pairs:.3g} pairs in {dt:.1f} s, fp64)"}
+    return base, {"rows": rows, "qrows": qrows, "s_ref": s_ref, "logp_ref": logp_ref}
+
+
+def parity_on_sample(w, ref, flags):
+    """Score of the mode on the sampled rows and KDE of the unshifted samples at the sampled queries, against the
+    oracle's values: per-point worst error as a multiple of the 1e-3 allowance, and the global figures."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import score_error
+    P, torch = w.P, w.torch
+    P.sdkde_score(w.xd, w.h, out=w.s, workspace=w.ws, flags=flags)
+    got = w.s[torch.from_numpy(ref["rows"]).to(w.s.device)].cpu().numpy()
+    worst, frob = score_error(got, ref["s_ref"])
+    _, logd = P.sdkde_eval(w.xd, w.qd, w.h, want="log", workspace=w.ws, flags=flags & ~32)
+    lp = logd[torch.from_numpy(ref["qrows"]).to(logd.device)].cpu().numpy().astype(np.float64)
+    return {"score_worst_of_allowance": worst, "score_rel_frobenius_vs_oracle": frob,
+            "max_abs_log_density_err_vs_oracle": float(np.max(np.abs(lp - ref["logp_ref"]))),
+            "rows": int(len(ref["rows"])), "queries": int(len(ref["qrows"])), "tolerance": 1e-3}
 
 
 def main():
@@ -67,175 +223,105 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="override the config's sample count (same distribution)")
     ap.add_argument("--m", type=int, default=None, help="override the config's query count")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-other-modes", action="store_true", help="skip the separately reported fp16x2-input mode")
+    ap.add_argument("--no-other-modes", action="store_true", help="skip the separately reported modes")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the block that times the other configs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)")
 
-    import numpy as np
     import torch
     import paper_2602_10378_amd as P
     import sdkde_inputs
 
-    cfg = sdkde_inputs.CONFIGS[args.config]
-    x, q, h = sdkde_inputs.make(args.config, seed=args.seed, n=args.n, m=args.m)
-    n, d = x.shape
-    m = q.shape[0]
     P.load()
-    dev = torch.device("cuda:0")
-    xd, qd = torch.from_numpy(x).to(dev), torch.from_numpy(q).to(dev)
-    ws = P.make_workspace(n, m, d, device=dev, flags=P.SDKDE_FLAG_SYMMETRIC)     # the largest footprint: serves every mode
-    s = torch.empty_like(xd)
-    x_sd = torch.empty_like(xd)
-    dens = torch.empty(m, dtype=torch.float32, device=dev)
-    logd = torch.empty(m, dtype=torch.float32, device=dev)
+    cfg = sdkde_inputs.CONFIGS[args.config]
+    w = Workload(P, torch, sdkde_inputs, args.config, args.seed, args.n, args.m)
+    n, m, d = w.n, w.m, w.d
+    main_run, plan = w.run(args.steps, args.warmup)
+    s_fp32, logd_fp32 = w.s.clone(), w.logd.clone()
+    default_shape = args.n is None and args.m is None
+    if main_run["roofline"]["bound"] == "mfma":
+        main_run["roofline"]["flops_per_launch"] = main_run["roofline"]["work_per_pair"]["mfma_f32"] * float(n) * n
+    traffic, traffic_detail = traffic_from_profile(args.config, plan) if default_shape else (None, None)
+    main_run["roofline"]["traffic"] = traffic
+    if traffic_detail:
+        main_run["roofline"]["traffic_detail"] = traffic_detail
 
-    def step(flags=P.SDKDE_PREC_FP32):
-        P.sdkde_score(xd, h, out=s, workspace=ws, flags=flags)
-        P.sdkde_debias(xd, s, h, out=x_sd)
-        P.sdkde_eval(x_sd, qd, h, density_out=dens, log_density_out=logd, workspace=ws, flags=flags)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    P.sdkde_profile_enable(True)      # HIP events around the main kernels, on the stream they run on
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # per-step spread (same stream)
-    t0 = time.perf_counter()
-    marks[0].record()
-    for k in range(args.steps):
-        step()
-        marks[k + 1].record()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    per_step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
-    score_launches, score_ms = P.sdkde_profile_summary(0)
-    eval_launches, eval_ms = P.sdkde_profile_summary(1)
-    P.sdkde_profile_enable(False)
-
-    s_fp32 = s.clone()
-    logd_fp32 = logd.clone()
-    other = None
-    fused = None
+    mode_steps = max(1, min(args.steps, 5))
+    other = {}
     if not args.no_other_modes:
-        # The same three steps through the one-call entry point (shift written by the score epilogue, one column
-        # mean for both passes: two launches fewer); fp32 path, same outputs.
-        def fused_step():
-            P.sdkde_fit_eval(xd, qd, h, score_out=s, samples_sd_out=x_sd, density_out=dens, log_density_out=logd, workspace=ws)
-        fused_step()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        for _ in range(args.steps):
-            fused_step()
-        torch.cuda.synchronize()
-        dtf = time.perf_counter() - t1
-        fused = {"value": (float(n) * n + float(m) * n) / (dtf / args.steps), "unit": "pairs/s",
-                 "ms_per_step": dtf / args.steps * 1e3,
-                 "max_abs_log_density_diff_vs_three_calls": float((logd - logd_fp32).abs().max()),
-                 "note": "sdkde_fit_eval: score, shift and eval in one call (fp32 path)"}
-    if not args.no_other_modes and d > 3:
-        # Lower-precision-input modes, reported separately: same steps, same timing protocol.
-        other = {}
-        notes = {"fp16x2_inputs": "cross-term inputs split into fp16 hi+lo on the fp16 matrix units, fp32 accumulate",
-                 "fp16x2_all": "both contractions on the fp16 matrix units (inputs and Phi split into fp16 hi+lo), "
-                               "fp32 accumulate, exp and row sums fp32",
-                 "symmetric_score": "fp32 path; the score computes each unordered pair of samples once (phi_ij = phi_ji) "
-                                    "and is still counted as n^2 pairs, as the paper counts them"}
-        modes = [("fp16x2_inputs", P.SDKDE_PREC_FP16X2)]
-        if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_PREC_FP16X2_ALL)["xt_scale"] == 2:      # else it runs as fp16x2 (d > 16)
-            modes.append(("fp16x2_all", P.SDKDE_PREC_FP16X2_ALL))
-        if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_FLAG_SYMMETRIC)["symmetric"]:
-            modes.append(("symmetric_score", P.SDKDE_FLAG_SYMMETRIC))
-        for key, flags in modes:
-            step(flags)
-            torch.cuda.synchronize()
-            P.sdkde_profile_enable(True)
-            t1 = time.perf_counter()
-            for _ in range(args.steps):
-                step(flags)
-            torch.cuda.synchronize()
-            dt16 = time.perf_counter() - t1
-            l16, ms16 = P.sdkde_profile_summary(0)
-            P.sdkde_profile_enable(False)
-            other[key] = {
-                "value": (float(n) * n + float(m) * n) / (dt16 / args.steps), "unit": "pairs/s",
-                "ms_per_step": dt16 / args.steps * 1e3, "score_pair_kernels_ms": ms16 / max(l16, 1),
-                "score_rel_frobenius_vs_fp32_path": float((s - s_fp32).norm() / s_fp32.norm()),
-                "max_abs_log_density_diff_vs_fp32_path": float((logd - logd_fp32).abs().max()),
-                "note": notes[key] + "; error vs the oracle is measured in tests/test_gpu_full_size.py"}
-    if not args.no_other_modes:
-        s.copy_(s_fp32)       # the sample check below is of the fp32 three-call path
+        fused, _ = w.run(mode_steps, 1, fn=w.fused_step)
+        fused["max_abs_log_density_diff_vs_three_calls"] = float((w.logd - logd_fp32).abs().max())
+        fused["note"] = "sdkde_fit_eval: score, shift and eval in one call (fp32 path)"
+        other["fused_call"] = fused
+        if not plan["thin"]:
+            modes = ["fp16x2"]
+            if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_PREC_FP16X2_ALL)["xt_scale"] == 2:      # else it runs as fp16x2 (d > 16)
+                modes.append("fp16x2_all")
+            if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_FLAG_SYMMETRIC)["symmetric"]:
+                modes.append("symmetric")
+            for mode in modes:
+                rec, _ = w.run(mode_steps, 1, mode=mode)
+                rec["score_rel_frobenius_vs_fp32_path"] = float((w.s - s_fp32).norm() / s_fp32.norm())
+                rec["max_abs_log_density_diff_vs_fp32_path"] = float((w.logd - logd_fp32).abs().max())
+                rec["note"] = MODE_NOTES[mode]
+                other[mode] = rec
 
-    pairs = float(n) * n + float(m) * n
     paper_s = PAPER_SECONDS.get((args.config, n, m))
-    ms_per_step = dt / args.steps * 1e3
-    value = pairs / (dt / args.steps)
-    score_avg_ms = score_ms / max(score_launches, 1)
-    eval_avg_ms = eval_ms / max(eval_launches, 1)
-    # algorithmic MFMA flops of the score kernel: 4d per pair (cross term 2d + Phi X 2d), n^2 pairs per launch
-    score_flops = 4.0 * d * float(n) * n
-    achieved = score_flops / (score_avg_ms * 1e-3) / 1e12
+    sec = main_run["ms_per_step"] * 1e-3
     out = {
-        "metric": "pair-interactions/sec (score n^2 + eval m*n)", "value": value, "unit": "pairs/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": (paper_s / (dt / args.steps)) if paper_s else None,
+        "metric": "pair-interactions/sec (score n^2 + eval m*n)", "value": main_run["value"], "unit": "pairs/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_run["ms_per_step"],
+        "higher_is_better": True, "scaling": None,
+        "vs_baseline": (paper_s / sec) if paper_s else None,
         "baseline_note": (f"paper: {paper_s:g} s end-to-end at this shape on one RTX A6000 with TF32 dots "
                           "(context, other hardware)") if paper_s else None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={n} samples, m={m} queries, d={d}, Gaussian mixture, "
-                               f"Silverman h={h:.4f}, score+debias+eval", "n": n, "m": m, "d": d, "seed": args.seed},
-        "end_to_end_s": dt / args.steps,
-        "ms_per_step_min": per_step_ms[0] if per_step_ms else None,
-        "ms_per_step_median": per_step_ms[len(per_step_ms) // 2] if per_step_ms else None,
-        "stages_ms": {"score_main_kernel": score_avg_ms, "eval_main_kernel": eval_avg_ms,
-                      "everything_else": ms_per_step - score_avg_ms - eval_avg_ms},
+                               f"Silverman h={w.h:.4f}, score+debias+eval", "n": n, "m": m, "d": d, "seed": args.seed},
+        "end_to_end_s": sec,
     }
-    if not P.sdkde_describe_plan(n, n, d, 0)["thin"]:
-        out["roofline"] = {"bound": "mfma", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                           "traffic": SCORE_KERNEL_TRAFFIC_BYTES.get(args.config) if (args.n is None and args.m is None) else None,
-                           "kernel": "pair_mfma_kernel (score)", "launch_ms": score_avg_ms,
-                           "flops_per_launch": score_flops,
-                           # per 16 x 16 tile of pairs: 8 d/16 MFMAs of 32 clocks, and 4 v_exp_f32 + 8 v_add_f32 that
-                           # cannot overlap them (fp32 MFMA and VALU do not co-issue on gfx950; measured by sdkde_peaks:
-                           # profiles/peaks_mfma_valu_coissue.txt, which times this mix at 333 clocks for d = 16:
-                           # 256 + 64 + 13 of switching between the two): the share of the time the MFMA pipe can have
-                           "frac_ceiling_of_instruction_mix": (256.0 * d / 16) / (256.0 * d / 16 + 4 * 8 + 8 * 4 + 13),
-                           "valu": {"exp_per_s": float(n) * n / (score_avg_ms * 1e-3),
-                                    "peak_exp_per_s": 256 * 4 * 16 * 2.4e9 / 2.0,
-                                    "note": "v_exp_f32: 8 clocks per wave instruction; sdkde_peaks measures 19.4e12/s back to back"}}
-    else:
-        # thin-d path (Appendix A): VALU bound.  Per score pair: d subs + d FMAs (r^2) + 1 add (D) + d FMAs
-        # (numerator) = 3d + 1 plain instructions, and one v_exp_f32 at a quarter of their rate (4 slots).  Peak:
-        # the chip's fp32 vector rate, 157.3 TFLOP/s = 78.6 T lane-instructions/s (256 CUs x 4 SIMDs x 32 lanes x
-        # 2.4 GHz: a wave instruction per 2 clocks per SIMD).  sdkde_peaks measures 62 (v_fma_f32) to 72 (v_add_f32)
-        # T lane-instructions/s for independent plain instructions from two or more waves, 19.4 for v_exp_f32, and
-        # 20.3 clocks for one exp and four FMAs issued in groups (16 at the published rates): the mix ceiling below.
-        slots = (3 * d + 1 + 4) * float(n) * n
-        peak = 256 * 4 * 32 * 2.4e9 / 1e12
-        ach = slots / (score_avg_ms * 1e-3) / 1e12
-        out["roofline"] = {"bound": "alu", "achieved": ach, "peak": peak, "unit": "T lane-slots/s", "frac": ach / peak,
-                           "traffic": None, "kernel": "pair_thin_kernel (score)", "launch_ms": score_avg_ms,
-                           "slots_per_pair": 3 * d + 5,
-                           "frac_ceiling_of_instruction_mix": (8.0 + 2.0 * (3 * d + 1)) / (8.1 + 3.05 * (3 * d + 1))}
-    if not P.sdkde_describe_plan(n, m, d, 2)["thin"]:
-        # the second kernel of the step, for completeness: 2d flops per pair (the cross term only); per tile 4 d/16
-        # MFMAs against the same VALU work as the score kernel
-        eval_tflops = 2.0 * d * float(m) * n / (eval_avg_ms * 1e-3) / 1e12
-        out["roofline_eval_kernel"] = {"bound": "mfma", "achieved": eval_tflops, "peak": PEAK_FP32_MFMA_TFLOPS,
-                                       "unit": "TFLOP/s", "frac": eval_tflops / PEAK_FP32_MFMA_TFLOPS,
-                                       "launch_ms": eval_avg_ms,
-                                       "frac_ceiling_of_instruction_mix": (128.0 * d / 16) / (128.0 * d / 16 + 4 * 8 + 8 * 4 + 6)}
-    if fused:
-        other = dict(other or {}, fused_call=fused)
+    for key in ("ms_per_step_min", "ms_per_step_median", "stages_ms", "roofline", "roofline_eval_kernel"):
+        out[key] = main_run[key]
+
+    if not args.no_cpu_baseline:
+        base, ref = oracle_sample(w)
+        out["cpu_baseline"] = base
+        out["parity_on_sample"] = parity_on_sample(w, ref, 0)
+        for mode in other:
+            if mode in MODE_FLAGS:
+                other[mode]["parity_on_sample"] = parity_on_sample(w, ref, MODE_FLAGS[mode])
     if other:
         out["other_modes"] = other
-    if not args.no_cpu_baseline:
-        base, s_rows = cpu_baseline(x, q, h)
-        out["cpu_baseline"] = base
-        got = s[: s_rows.shape[0]].cpu().numpy().astype(np.float64)
-        out["parity_on_sample"] = {"score_rel_frobenius": float(np.linalg.norm(got - s_rows) / np.linalg.norm(s_rows)),
-                                   "rows": int(s_rows.shape[0])}
+
+    if not args.no_per_config and default_shape:
+        # The other configs, timed in this process with the same protocol (three calls per step; the one-call
+        # entry point beside them, which is what a small problem should use): driver-visible numbers per config.
+        del w, s_fp32, logd_fp32
+        torch.cuda.empty_cache()
+        per = {}
+        shapes = [(name, None, None) for name in ("C1", "C2", "C3", "C4", "C5") if name != args.config]
+        shapes.append(("C2", 32768, 4096))          # the shape of the paper's runtime table
+        for name, n_o, m_o in shapes:
+            wc = Workload(P, torch, sdkde_inputs, name, args.seed, n_o, m_o)
+            est = wc.pairs / 1.5e12                                  # seconds per step, roughly
+            k = int(max(3, min(200, 0.6 / max(est, 1e-6))))
+            rec, plan_c = wc.run(k, 3)
+            fused, _ = wc.run(k, 3, fn=wc.fused_step)
+            rec["fused_call_ms_per_step"] = fused["ms_per_step"]
+            rec["fused_call_value"] = fused["value"]
+            rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
+            traffic, detail = traffic_from_profile(name, plan_c) if (n_o is None and m_o is None) else (None, None)
+            rec["roofline"]["traffic"] = traffic
+            if detail:
+                rec["roofline"]["traffic_detail"] = detail
+            ps = PAPER_SECONDS.get((name, wc.n, wc.m))
+            if ps:
+                rec["paper_seconds_other_hardware"] = ps
+            per[name if n_o is None else f"{name}_n{wc.n}_m{wc.m}"] = rec
+            del wc
+            torch.cuda.empty_cache()
+        out["per_config"] = per
     print(json.dumps(out))
 
 

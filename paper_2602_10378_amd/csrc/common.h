@@ -20,7 +20,7 @@ constexpr int kTile = 16;              // MFMA 16x16x4 tile edge
 constexpr int kRowPad = 1024;          // row padding of every prepared array (>= rows per workgroup)
 constexpr float kPadNorm = -1.0e30f;   // "-|x|^2" of a padding sample: exp2 of it is exactly 0
 constexpr float kPadCoord = 1.0e18f;   // thin-d padding coordinate: squared distance ~1e36, exp2(-that) = 0
-constexpr int kMeanBlocks = 128;
+constexpr int kCentreElems = 4096;      // the centre is the mean of about this many evenly strided input values
 constexpr int kFlushTiles = 64;         // sample tiles between folds of the running sums (power of two)
 constexpr int kThinMaxDScore = 6;      // direct-difference path for the score kinds up to this d, MFMA path above
 constexpr int kThinMaxDEval = 3;       // the same for the kinds without a numerator (eval, Laplace eval)

@@ -1,4 +1,4 @@
-// Pair kernels of the matrix path (d >= 4): pair_mfma_kernel, pair_diag_kernel and their operand helpers.
+// Pair kernel of the matrix path (d >= 4): pair_mfma_kernel and its operand helpers.
 #pragma once
 #include "common.h"
 
@@ -25,8 +25,9 @@ namespace {
 //
 // SELF (score at the samples themselves): the pair (i, i) must stay out of D and T, because
 // T_i/D_i - x_i would otherwise cancel against the large self term whenever a point has few
-// neighbours; the epilogue restores it analytically (phi_ii = 1).  This kernel therefore skips
-// the NI sample tiles that are the wave's own row tiles; pair_diag_kernel covers them.
+// neighbours; the epilogue restores it analytically (phi_ii = 1).  The pipelined loop therefore skips
+// the NI sample tiles that are the wave's own row tiles (no masking code in the hot loop); a plain loop after it
+// pairs the row tiles with those own tiles that lie in this workgroup's split, the diagonal masked.
 //
 // Grid: blockIdx.x = row_block * S + split; each workgroup handles RB = 64*NI rows and the
 // sample tiles [split*tiles_per_split, min(ntiles, (split+1)*tiles_per_split)).  With S a
@@ -366,109 +367,71 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         dsum[t] = ROWMAX ? fmaxf(dsum[t], dacc[t]) : dsum[t] + dacc[t];
 #pragma unroll
         for (int mb = 0; mb < KT; ++mb) tsum[t][mb] += tacc[t][mb];
-        if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
-            constexpr float unscale = 1.0f / (float)(1 << kPhiScaleLog2);
+    }
+    if constexpr (SELF) {
+        // The wave's own row tiles taken as samples, as far as they lie in this split: every pair but that of a
+        // point with itself.  A plain loop: NI * 16 of a row's n pairs.
+        const int d_end = min(t_end, dt0 + NI);
+        for (int jt = max(t_begin, dt0); jt < d_end; ++jt) {
+            const int dt = jt - dt0;
+            f32x4 a1[KB], a2[KB], a2lo[HALF2 ? KB : 1];
+            const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
+            if (!HALF2) {
+                const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * kTile);
+            } else {
+                const float* trow = xt + (((int64_t)jt * DP + r) * 4 + g) * 8;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * 32);
+                    a2lo[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * 32 + 4);
+                }
+            }
+            const f32x4 nj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
+#pragma unroll
+            for (int t = 0; t < NI; ++t) {
+                f32x4 c = nj + ni[t];
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) c = rows.cross(t, kb, a1[kb], c);
+                f32x4 phi;
+                // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
+                const bool own = t == dt;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float e = __builtin_amdgcn_exp2f(c[v]);
+                    phi[v] = (own && g * 4 + v == r) ? 0.0f : e;
+                }
+                dsum[t] += (phi.x + phi.y) + (phi.z + phi.w);
+                if (!HALF2) {
+#pragma unroll
+                    for (int mb = 0; mb < KB; ++mb)
+#pragma unroll
+                        for (int v = 0; v < 4; ++v)
+                            tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tsum[t][mb], 0, 0, 0);
+                } else {
+                    const f16x8 bphi = split_phi(phi);
+#pragma unroll
+                    for (int mb = 0; mb < KB; ++mb) {
+                        tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2[mb]), bphi, tsum[t][mb], 0, 0, 0);
+                        tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2lo[mb]), bphi, tsum[t][mb], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+    if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
+        constexpr float unscale = 1.0f / (float)(1 << kPhiScaleLog2);
+#pragma unroll
+        for (int t = 0; t < NI; ++t) {
             dsum[t] *= unscale;
 #pragma unroll
             for (int mb = 0; mb < KT; ++mb) tsum[t][mb] *= unscale;
         }
     }
     store_partials<KB, NI, SCORE, ROWMAX>(part_t, part_d, split, m_pad, row0, r, g, tsum, dsum);
-}
-
-// Diagonal blocks of the score at the samples themselves: every wave pairs its NI row tiles with
-// the same NI tiles taken as samples, leaving out the pair of each point with itself, and writes
-// the sums into partial slot `slot` (one past the splits of pair_mfma_kernel).  Same operand
-// layouts as above; a plain loop, since this is NI*16 pairs per row out of n.
-// Grid: one workgroup per row block, as in the main kernel.
-template <int KB, int NI, int PREC>
-__global__ __launch_bounds__(kBlock) void pair_diag_kernel(
-    const float* __restrict__ xs, const float* __restrict__ xt, const float* __restrict__ xn,
-    float* __restrict__ part_t, float* __restrict__ part_d, int ntiles, int slot, int64_t m_pad)
-{
-    constexpr int DP = KB * 16;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);    // wave-uniform by construction
-    const int r = lane & 15, g = lane >> 4;
-    const int64_t row0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * (NI * kTile);
-    const int dt0 = (int)(row0 / kTile);
-
-    RowTiles<KB, NI, PREC> rows;
-    rows.load(xs, xn, row0, r, g);
-    if (PREC == SDKDE_PREC_FP16X2_ALL) {      // Phi carries 2^kPhiScaleLog2, as in pair_mfma_kernel
-#pragma unroll
-        for (int t = 0; t < NI; ++t) rows.ni[t] += (float)kPhiScaleLog2;
-    }
-    f32x4 tsum[NI][KB];
-    float dsum[NI];
-#pragma unroll
-    for (int t = 0; t < NI; ++t) {
-        dsum[t] = 0.0f;
-#pragma unroll
-        for (int mb = 0; mb < KB; ++mb) tsum[t][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
-
-    for (int dt = 0; dt < NI; ++dt) {
-        const int jt = dt0 + dt;
-        if (jt >= ntiles) break;               // rows past the last sample tile are padding
-        constexpr bool HALF2 = PREC == SDKDE_PREC_FP16X2_ALL;
-        f32x4 a1[KB], a2[KB], a2lo[HALF2 ? KB : 1];
-        const float* xrow = xs + ((int64_t)jt * kTile + r) * DP + g * 4;
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb) a1[kb] = *reinterpret_cast<const f32x4*>(xrow + kb * 16);
-        if (!HALF2) {
-            const float* trow = xt + ((int64_t)jt * DP + r) * kTile + g * 4;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * kTile);
-        } else {
-            const float* trow = xt + (((int64_t)jt * DP + r) * 4 + g) * 8;
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) {
-                a2[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * 32);
-                a2lo[kb] = *reinterpret_cast<const f32x4*>(trow + kb * 16 * 32 + 4);
-            }
-        }
-        const f32x4 nj = *reinterpret_cast<const f32x4*>(xn + (int64_t)jt * kTile + g * 4);
-#pragma unroll
-        for (int t = 0; t < NI; ++t) {
-            f32x4 c = nj + rows.ni[t];
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) c = rows.cross(t, kb, a1[kb], c);
-            f32x4 phi;
-            // register v of lane (r, g) is the pair (sample 4g + v, row r) of this tile
-            const bool own = t == dt;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const float e = __builtin_amdgcn_exp2f(c[v]);
-                phi[v] = (own && g * 4 + v == r) ? 0.0f : e;
-            }
-            dsum[t] += (phi.x + phi.y) + (phi.z + phi.w);
-            if (!HALF2) {
-#pragma unroll
-                for (int mb = 0; mb < KB; ++mb)
-#pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a2[mb][v], phi[v], tsum[t][mb], 0, 0, 0);
-            } else {
-                const f16x8 bphi = split_phi(phi);
-#pragma unroll
-                for (int mb = 0; mb < KB; ++mb) {
-                    tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2[mb]), bphi, tsum[t][mb], 0, 0, 0);
-                    tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2lo[mb]), bphi, tsum[t][mb], 0, 0, 0);
-                }
-            }
-        }
-    }
-    if (PREC == SDKDE_PREC_FP16X2_ALL) {
-        constexpr float unscale = 1.0f / (float)(1 << kPhiScaleLog2);
-#pragma unroll
-        for (int t = 0; t < NI; ++t) {
-            dsum[t] *= unscale;
-#pragma unroll
-            for (int mb = 0; mb < KB; ++mb) tsum[t][mb] *= unscale;
-        }
-    }
-    store_partials<KB, NI, true>(part_t, part_d, slot, m_pad, row0, r, g, tsum, dsum);
 }
 
 }  // namespace

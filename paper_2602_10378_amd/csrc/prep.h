@@ -1,54 +1,63 @@
-// Prep kernels: column means, then centre + scale + pad (+ fp16 hi/lo split) into the layouts the pair kernels read.
+// Prep kernels: centre + scale + pad (+ fp16 hi/lo split) into the layouts the pair kernels read.
 #pragma once
 #include "common.h"
 
 namespace {
 
 // ------------------------------------------------------------------------------------------
-// Prep: column means (deterministic two-stage reduction), then centre + scale + pad.
+// Prep: the centre (mean of a strided subsample, formed by every workgroup for itself), then centre + scale + pad.
 // ------------------------------------------------------------------------------------------
 
-// partial[b][c] = sum over this block's rows of x[row][c], double accumulation.
-__global__ __launch_bounds__(kBlock) void mean_partial_kernel(const float* __restrict__ x, int64_t n,
-                                                              int d, double* __restrict__ partial)
+// The centre all coordinates are taken relative to: the column means of an evenly strided subsample of the
+// samples (about kCentreElems input values, at least 32 rows), summed in double in a fixed order, so every
+// workgroup that computes it gets the same bits.  Any point near the data serves (the exponent
+// -|p - x|^2 / 2h^2 does not depend on it; it only keeps the norms of the Gram expansion small), so a few hundred
+// rows spread over the whole array are as good as all of them and need no pass of their own.
+// Result in smean[0 .. d); ends with a barrier.
+__device__ __forceinline__ int64_t centre_rows(int64_t n, int d)
 {
-    __shared__ double red[kBlock];
-    const int rows_per_iter = kBlock / d;              // d <= 128 < kBlock
-    const int rr = threadIdx.x / d, c = threadIdx.x % d;
-    double acc = 0.0;
-    if (rr < rows_per_iter) {
-        for (int64_t row = (int64_t)blockIdx.x * rows_per_iter + rr; row < n;
-             row += (int64_t)gridDim.x * rows_per_iter)
-            acc += (double)x[row * d + c];
-    }
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    if ((int)threadIdx.x < d) {
-        double s = 0.0;
-        for (int r = 0; r < rows_per_iter; ++r) s += red[r * d + threadIdx.x];
-        partial[(int64_t)blockIdx.x * d + threadIdx.x] = s;
-    }
+    const int64_t want = kCentreElems / d > 32 ? kCentreElems / d : 32;
+    return n < want ? n : want;
 }
 
-// Second stage of the column mean, done by every prep workgroup for itself (saves a launch):
-// sums the kMeanBlocks partials of each column in a fixed order, so all workgroups get the same
-// bits.  Result in smean[0 .. d); ends with a barrier.
-__device__ __forceinline__ void block_mean(const double* __restrict__ partial, int d, int64_t n, double* red,
-                                           float* smean)
+__device__ __forceinline__ void block_centre(const float* __restrict__ src, int64_t n, int d, double* red, float* smean)
 {
-    const int slices = kBlock / d;                        // d <= 128, so >= 2
-    const int sl = threadIdx.x / d, c = threadIdx.x % d;
+    const int rows_per_iter = kBlock / d;                 // d <= 128 < kBlock
+    const int rr = threadIdx.x / d, c = threadIdx.x % d;
+    const int64_t rows = centre_rows(n, d);
+    const int64_t stride = n / rows;                      // >= 1
     double acc = 0.0;
-    if (sl < slices)
-        for (int b = sl; b < kMeanBlocks; b += slices) acc += partial[(int64_t)b * d + c];
+    if (rr < rows_per_iter) {
+#pragma unroll 4
+        for (int64_t k = rr; k < rows; k += rows_per_iter) acc += (double)src[k * stride * d + c];
+    }
     red[threadIdx.x] = acc;
     __syncthreads();
     if ((int)threadIdx.x < d) {
         double t = 0.0;
-        for (int q = 0; q < slices; ++q) t += red[q * d + threadIdx.x];
-        smean[threadIdx.x] = (float)(t / (double)n);
+        for (int q = 0; q < rows_per_iter; ++q) t += red[q * d + threadIdx.x];
+        smean[threadIdx.x] = (float)(t / (double)rows);
     }
     __syncthreads();
+}
+
+// Where a prep launch gets the centre from.
+struct PrepCommon {
+    const float* centre_src;   // samples to take the centre of (centre_rows of them, strided); null: read `centre`
+    int64_t centre_n;          // rows of centre_src
+    float* centre;             // in the workspace: written by workgroup 0 when computed, read otherwise
+};
+
+// Centre into smean (computed or read back).  Ends with a barrier.
+__device__ __forceinline__ void prep_common(const PrepCommon& pc, int d, double* red, float* smean)
+{
+    if (pc.centre_src) {
+        block_centre(pc.centre_src, pc.centre_n, d, red, smean);
+        if (blockIdx.x == 0 && (int)threadIdx.x < d) pc.centre[threadIdx.x] = smean[threadIdx.x];
+    } else {
+        if ((int)threadIdx.x < d) smean[threadIdx.x] = pc.centre[threadIdx.x];
+        __syncthreads();
+    }
 }
 
 // One array to prepare: src[rows][d] -> dst (rows_pad rows), optional blocked transpose dst_t, norms dst_n.
@@ -102,10 +111,9 @@ constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (tw
 // prec == SDKDE_PREC_FP16X2_ALL: dst_t holds fp16 pairs too, laid out as the A operand of the K = 32
 // second contraction: for tile, column c and lane group g, eight halves [hi(4g..4g+3) | the same again]
 // followed by eight halves [lo(4g..4g+3) | the same again] (twice the bytes of the fp32 layout).
-// Grid: job0's blocks first (blocks0 of them), then job1's; sample mean from mean_partial.
+// Grid: job0's blocks first (blocks0 of them), then job1's.
 __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
-                                                           const double* __restrict__ mean_partial, int64_t n_mean,
-                                                           float a, int prec, Stamp stamp)
+                                                           PrepCommon common, float a, int prec, Stamp stamp)
 {
     __shared__ double red[kBlock];
     __shared__ float smean[SDKDE_MAX_D];
@@ -113,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
     __shared__ float used[kPrepRows][SDKDE_MAX_D + 1];    // the value the first contraction multiplies (hi + lo, or raw)
     __shared__ int stamp_flag;
     const bool poisoned = stamp_poisons(stamp, &stamp_flag);
-    block_mean(mean_partial, d, n_mean, red, smean);
+    prep_common(common, d, red, smean);
 
     const bool second = (int)blockIdx.x >= blocks0;
     const PrepJob& job = second ? job1 : job0;
@@ -167,14 +175,13 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
 // Thin-d variant: dst[row][d] = a (x - mean), padding rows get pad_value in every coordinate.
 // One thread per padded row; same two-job grid.
 __global__ __launch_bounds__(kBlock) void prep_thin_kernel(PrepJob job0, PrepJob job1, int blocks0, int d,
-                                                           const double* __restrict__ mean_partial, int64_t n_mean,
-                                                           float a, Stamp stamp)
+                                                           PrepCommon common, float a, Stamp stamp)
 {
     __shared__ double red[kBlock];
     __shared__ float smean[SDKDE_MAX_D];
     __shared__ int stamp_flag;
     const bool poisoned = stamp_poisons(stamp, &stamp_flag);
-    block_mean(mean_partial, d, n_mean, red, smean);
+    prep_common(common, d, red, smean);
     const bool second = (int)blockIdx.x >= blocks0;
     const PrepJob& job = second ? job1 : job0;
     const int64_t row = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kBlock + threadIdx.x;

@@ -329,7 +329,7 @@ void apply_symmetric(Plan& p, int64_t n, uint32_t flags, bool self)
 }
 
 struct Workspace {
-    double* mean_partial;
+    float* centre;                         // the point all coordinates are taken relative to (prep.h)
     uint64_t* stamp;                       // record of the last sample preparation (prep.h)
     float* xs;  float* xt;  float* xn;     // samples: scaled rows, blocked transpose, -|x|^2
     float* ps;  float* pn;                 // evaluation points (alias xs/xn when they are the samples)
@@ -349,7 +349,7 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base, ui
         off += (bytes + 255) / 256 * 256;
         return base ? (char*)base + at : (char*)nullptr;
     };
-    w.mean_partial = (double*)take(sizeof(double) * kMeanBlocks * SDKDE_MAX_D);
+    w.centre = (float*)take(sizeof(float) * SDKDE_MAX_D);
     w.stamp = (uint64_t*)take(sizeof(uint64_t) * kStampWords);
     w.xs = (float*)take(sizeof(float) * p.n_pad * p.dp);
     // blocked transpose for the second contraction: fp32, or hi/lo fp16 pairs stored twice (2x the bytes)
@@ -364,9 +364,9 @@ Workspace layout(const Plan& p, bool score, bool separate_points, void* base, ui
         w.ps = w.xs;
         w.pn = w.xn;
     }
-    // one slot per split, plus the diagonal-block slot of the score at the samples themselves
-    size_t slots = (size_t)p.nsplit + ((score && !separate_points && !p.thin) ? 1 : 0);
-    if (p.sym_on) slots = (size_t)p.sym_ngroups + 3;     // pair_sym_kernel's, then the in-block pass and its diagonal
+    // one slot per split
+    size_t slots = (size_t)p.nsplit;
+    if (p.sym_on) slots = (size_t)p.sym_ngroups + 2;     // pair_sym_kernel's, then the in-block pass
     w.part_t = score ? (float*)take(sizeof(float) * slots * p.m_pad * p.dp) : nullptr;
     w.part_d = (float*)take(sizeof(float) * slots * p.m_pad);
     w.bytes = off;
@@ -428,16 +428,13 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
         } else {                                                                                                  \
             SDKDE_LAUNCH_MFMA_K(KB_, NI_, 4);                                                                     \
         }                                                                                                         \
-        if constexpr (KIND == kScoreSelf || KIND == kScoreBand)                                                   \
-            hipLaunchKernelGGL((pair_diag_kernel<KB_, NI_, PREC>), dim3((unsigned)p.row_blocks), block, 0, st,   \
-                               w.xs, w.xt, w.xn, w.part_t, w.part_d, p.ntiles, p.nsplit, p.m_pad);                \
     } while (0)
 #define SDKDE_LAUNCH_THIN(D_, R_)                                                                      \
     do {                                                                                               \
         if constexpr (KIND != kScoreBand)                                                              \
             hipLaunchKernelGGL((pair_thin_kernel<D_, R_, KIND>), grid, block, 0, st, w.ps, w.xs,       \
                                w.part_t, w.part_d, p.ntiles, p.tiles_per_split, p.nsplit, p.m_pad,     \
-                               laplace_c0, shift);                                                     \
+                               laplace_c0, shift);                                               \
     } while (0)
 // d = 4 .. 6: the kinds a score call runs (one row per thread)
 #define SDKDE_LAUNCH_THIN_SCORE(D_)                                                                    \
@@ -542,7 +539,7 @@ int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, const fl
 }
 
 // Symmetric mode: pairs across blocks (pair_sym_kernel), then the pairs inside each block with the ordinary
-// kernels restricted to the block (slots ngroups + 1 and ngroups + 2).
+// kernel restricted to the block (slot ngroups + 1).
 template <int KB, int NI, int PREC, int KLAST>
 int launch_sym_kernel(const Plan& p, const Workspace& w, hipStream_t st)
 {
@@ -638,15 +635,9 @@ int launch_max_shift(const Plan& p, const Workspace& w, uint32_t flags, hipStrea
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
-// First stage of the column means of src[rows][d] (the prep kernels finish them).
-int launch_mean(const float* src, int64_t rows, int d, const Workspace& w, hipStream_t st)
-{
-    hipLaunchKernelGGL(mean_partial_kernel, dim3(kMeanBlocks), dim3(kBlock), 0, st, src, rows, d, w.mean_partial);
-    return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
-}
-
 // Centre/scale/pad one or two arrays in a single launch (second.src == nullptr: only the first).
-// n_mean: number of rows the column means in w.mean_partial were taken over.
+// centre_src: the samples whose strided subsample gives the centre (also left in w.centre); null: w.centre as an
+// earlier launch on this workspace left it.
 // What identifies prepared samples: the kind of call that prepared them (the score and eval layouts differ), the
 // caller's array, its shape, the precision mode and the scale a = sqrt(log2 e / 2) / h as it reached the kernels.
 Stamp make_stamp(const Workspace& w, bool check, bool score, const float* samples, int64_t n, int d, uint32_t prec, float a)
@@ -661,9 +652,10 @@ Stamp make_stamp(const Workspace& w, bool check, bool score, const float* sample
     return s;
 }
 
-int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int64_t n_mean, float a,
-                const Workspace& w, uint32_t flags, const Stamp& stamp, hipStream_t st)
+int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, const float* centre_src, int64_t centre_n,
+                float a, const Workspace& w, uint32_t flags, const Stamp& stamp, hipStream_t st)
 {
+    const PrepCommon common{centre_src, centre_n, w.centre};
     const int64_t per_block = p.thin ? kBlock : kPrepRows;
     if (first.rows_pad % per_block || (second.src && second.rows_pad % per_block)) return SDKDE_EINVAL;
     const int64_t blocks0 = first.rows_pad / per_block;
@@ -671,11 +663,10 @@ int launch_prep(const Plan& p, const PrepJob& first, const PrepJob& second, int6
     if (blocks0 + blocks1 > 0x7fffffffLL) return SDKDE_EUNSUPPORTED;
     const dim3 grid((unsigned)(blocks0 + blocks1)), block(kBlock);
     if (p.thin)
-        hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, w.mean_partial,
-                           n_mean, a, stamp);
+        hipLaunchKernelGGL(prep_thin_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, common, a, stamp);
     else
-        hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, p.dp,
-                           w.mean_partial, n_mean, a, (int)effective_prec(flags, p.thin, p.dp), stamp);
+        hipLaunchKernelGGL(prep_mfma_kernel, grid, block, 0, st, first, second, (int)blocks0, p.d, p.dp, common, a,
+                           (int)effective_prec(flags, p.thin, p.dp), stamp);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 
@@ -724,17 +715,16 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     hipStream_t st = (hipStream_t)stream;
 
     const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));   // sqrt(c log2 e)
+    // at the samples themselves the largest weight is the self pair (exponent 0): nothing to shift
+    const bool shifted = !self && (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
     // When the points are the samples (m == n, so m_pad == n_pad), one prepared array serves
     // as both operands.
-    if ((rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
     const PrepJob sample_job{samples, n, p.n_pad, w.xs, w.xt, w.xn, kPadCoord};
     const PrepJob point_job{self ? nullptr : points, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
     const Stamp stamp = make_stamp(w, false, true, samples, n, d, effective_prec(flags, p.thin, p.dp), (float)a);
-    if ((rc = launch_prep(p, sample_job, point_job, n, (float)a, w, flags, stamp, st)) != SDKDE_OK) return rc;
+    if ((rc = launch_prep(p, sample_job, point_job, samples, n, (float)a, w, flags, stamp, st)) != SDKDE_OK) return rc;
 
     if ((rc = profile_mark(0, 0, st)) != SDKDE_OK) return rc;
-    // at the samples themselves the largest weight is the self pair (exponent 0): nothing to shift
-    const bool shifted = !self && (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
     if (shifted && (rc = launch_max_shift(p, w, flags, st)) != SDKDE_OK) return rc;
     const float* shift = shifted ? w.shift : nullptr;
     rc = p.sym_on ? launch_symmetric(p, w, flags, st)
@@ -744,21 +734,21 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
     if ((rc = profile_mark(0, 1, st)) != SDKDE_OK) return rc;
 
     const int64_t total = m * (int64_t)d;
-    const float inv_ah2 = (float)(1.0 / (a * h * h));
-    const int nslots = p.sym_on ? p.sym_ngroups + 3 : p.nsplit + ((self && !p.thin) ? 1 : 0);
+    const int nslots = p.sym_on ? p.sym_ngroups + 2 : p.nsplit;
+    const int mode = p.thin ? 1 : (self ? 2 : 0);        // see score_epilogue_kernel
     const int ps_halves = effective_prec(flags, p.thin, p.dp) != SDKDE_PREC_FP32 ? 1 : 0;
+    const float inv_ah2 = (float)(1.0 / (a * h * h)), half_h2 = (float)(0.5 * h * h);
     if (!p.thin && epilogue_parts(nslots, total) == kEpiPartsFew) {
         const int64_t quads = m * (p.dp / 4);
         constexpr int per_wg = kBlock / kEpiPartsFew;
         const uintptr_t io = (uintptr_t)score_out | (uintptr_t)samples_sd_out | (samples_sd_out ? (uintptr_t)samples : 0);
         const int quad_io = (d % 4 == 0 && (io & 15) == 0) ? 1 : 0;
         hipLaunchKernelGGL(score_epilogue_quad_kernel, dim3((unsigned)((quads + per_wg - 1) / per_wg)), dim3(kBlock), 0, st,
-                           w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp, self ? 2 : 0, ps_halves, inv_ah2, score_out,
-                           samples, (float)(0.5 * h * h), samples_sd_out, quad_io);
+                           w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp, mode, ps_halves, inv_ah2, score_out,
+                           samples, half_h2, samples_sd_out, quad_io);
     } else {
         SDKDE_LAUNCH_EPILOGUE(score_epilogue_kernel, nslots, total, st, w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d,
-                              p.dp, p.thin ? 1 : (self ? 2 : 0), ps_halves, inv_ah2, score_out, samples,
-                              (float)(0.5 * h * h), samples_sd_out);
+                              p.dp, mode, ps_halves, inv_ah2, score_out, samples, half_h2, samples_sd_out);
     }
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
@@ -766,7 +756,7 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
 // Shared body of sdkde_eval and sdkde_eval_laplace.
 int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
               float* density_out, float* log_density_out, void* workspace, size_t workspace_bytes, uint32_t flags,
-              void* stream, bool laplace, bool reuse_mean = false)
+              void* stream, bool laplace, bool reuse_centre = false)
 {
     int rc = check_common(samples, n, m, d, h, flags);
     if (rc != SDKDE_OK) return rc;
@@ -781,30 +771,30 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     hipStream_t st = (hipStream_t)stream;
 
     const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
-    // reuse_mean: w.mean_partial still holds the column sums of an earlier pass over (nearly) the same points
+    const bool shifted = (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
     const PrepJob sample_job{samples, n, p.n_pad, w.xs, nullptr, w.xn, kPadCoord};
     const PrepJob query_job{queries, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
     if (flags & SDKDE_FLAG_SAMPLES_PREPARED) {
-        // the workspace still holds the column sums and the prepared samples (their place in the workspace depends
+        // the workspace still holds the centre and the prepared samples (their place in the workspace depends
         // on n, d and the precision mode only, not on m): only the queries are prepared
         // (a call whose record of the prepared samples does not match gets NaN for every output)
         const Stamp expect = make_stamp(w, true, false, samples, n, d, effective_prec(flags, p.thin, p.dp), (float)a);
-        if ((rc = launch_prep(p, query_job, PrepJob{}, n, (float)a, w, flags, expect, st)) != SDKDE_OK) return rc;
+        if ((rc = launch_prep(p, query_job, PrepJob{}, nullptr, 0, (float)a, w, flags, expect, st)) != SDKDE_OK) return rc;
     } else {
-        if (!reuse_mean && (rc = launch_mean(samples, n, d, w, st)) != SDKDE_OK) return rc;
+        // reuse_centre: w.centre still holds the centre of an earlier pass over (nearly) the same points
         const Stamp stamp = make_stamp(w, false, false, samples, n, d, effective_prec(flags, p.thin, p.dp), (float)a);
-        if ((rc = launch_prep(p, sample_job, query_job, n, (float)a, w, flags, stamp, st)) != SDKDE_OK) return rc;
+        if ((rc = launch_prep(p, sample_job, query_job, reuse_centre ? nullptr : samples, n, (float)a, w, flags, stamp, st)) != SDKDE_OK)
+            return rc;
     }
 
+    const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
     if ((rc = profile_mark(1, 0, st)) != SDKDE_OK) return rc;
-    const bool shifted = (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
     if (shifted && (rc = launch_max_shift(p, w, flags, st)) != SDKDE_OK) return rc;
     const float* shift = shifted ? w.shift : nullptr;
     rc = laplace ? launch_pair_prec<kEvalLaplace>(p, w, flags, shift, st) : launch_pair_prec<kEval>(p, w, flags, shift, st);
     if (rc != SDKDE_OK) return rc;
     if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
 
-    const double lognorm = -log((double)n) - (double)d * log(h) - 0.5 * (double)d * log(6.283185307179586476925286766559);
     SDKDE_LAUNCH_EPILOGUE(eval_epilogue_kernel, p.nsplit, m, st, w.part_d, p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0,
                           shift, density_out, log_density_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
@@ -876,8 +866,8 @@ int sdkde_fit_eval(const float* samples, int64_t n, const float* queries, int64_
     if (m > 0 && (!queries || (!density_out && !log_density_out))) return SDKDE_EINVAL;
     rc = score_impl(samples, n, nullptr, n, d, h, score_out, samples_sd_out, workspace, workspace_bytes, flags, stream);
     if (rc != SDKDE_OK || m == 0) return rc;
-    // The column means of the samples are still in the workspace; the shifted samples are centred on them
-    // too (any centre is exact, it only has to be near the data), which saves the mean pass.
+    // The centre of the samples is still in the workspace; the shifted samples are centred on it too (any
+    // centre is exact, it only has to be near the data).
     return eval_impl(samples_sd_out, n, queries, m, d, h, density_out, log_density_out, workspace, workspace_bytes,
                      flags, stream, false, true);
 }
@@ -940,7 +930,7 @@ int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t 
     char* const base = reinterpret_cast<char*>(uintptr_t(1) << 20);      // any aligned non-null address: offsets only
     const Workspace w = layout(p, score, separate, base, flags);
     auto off = [&](const void* q) { return q ? (int64_t)((const char*)q - base) : (int64_t)-1; };
-    const int64_t slots = p.sym_on ? p.sym_ngroups + 3 : p.nsplit + ((score && !separate && !p.thin) ? 1 : 0);
+    const int64_t slots = p.sym_on ? p.sym_ngroups + 2 : p.nsplit;
     const int64_t xt_scale = effective_prec(flags, p.thin, p.dp) == SDKDE_PREC_FP16X2_ALL ? 2 : 1;
     const int64_t v[20] = {
         p.thin ? 1 : 0, p.dp, p.ni, p.rows_per_block, p.row_blocks, p.nsplit, p.tiles_per_split, p.ntiles,

@@ -123,6 +123,20 @@ def standard_normal_cloud(rows: int, d: int, seed: int = 0, scale: float = 1.0) 
     return out
 
 
+def sample_rows(count: int, extra: int, seed: int = 0) -> np.ndarray:
+    """Row indices for sampled checks at sizes where the oracle cannot cover every row: `extra` random rows plus
+    the rows next to tile, row-block and split boundaries (first and last rows, powers of two and their
+    neighbours from both ends, the eighths of the range).  Sorted, unique."""
+    edges = [0, 1, 15, 16, 17, 63, 64, 127, 128, 255, 256, 511, 512, 1023, 1024, 2047, 2048]
+    rows = {e for e in edges if e < count}
+    rows |= {count - 1 - e for e in edges if e < count}
+    rows |= {(count // 8) * k for k in range(1, 8)} | {(count // 8) * k - 1 for k in range(1, 8)}
+    rows = {r for r in rows if 0 <= r < count}
+    rng = np.random.default_rng(seed)
+    rows |= set(int(v) for v in rng.integers(0, count, size=extra))
+    return np.array(sorted(rows), dtype=np.int64)
+
+
 def make(name: str, seed: int = 0, n: int | None = None, m: int | None = None):
     """Inputs of a named config; n/m may be overridden to get a scaled-down case of the
     same distribution."""

@@ -11,15 +11,7 @@ from parity import assert_density_close, assert_log_density_close, assert_score_
 pytestmark = pytest.mark.gpu
 
 
-def _sample_rows(count, extra, seed=0):
-    edges = [0, 1, 15, 16, 17, 63, 64, 127, 128, 255, 256, 511, 512, 1023, 1024, 2047, 2048]
-    rows = {e for e in edges if e < count}
-    rows |= {count - 1 - e for e in edges if e < count}
-    # sample-tile ranges of the splits start at multiples of (tiles per split) * 16
-    rows |= {(count // 8) * k for k in range(1, 8)} | {(count // 8) * k - 1 for k in range(1, 8)}
-    rng = np.random.default_rng(seed)
-    rows |= set(int(v) for v in rng.integers(0, count, size=extra))
-    return np.array(sorted(rows), dtype=np.int64)
+_sample_rows = sdkde_inputs.sample_rows      # random rows plus those at tile / row-block / split boundaries
 
 
 @pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
