@@ -109,6 +109,24 @@ def true_log_density(q, weights, means, variances) -> np.ndarray:
     return top + np.log(np.exp(logs - top).sum(0))
 
 
+def draw_from_mixture(weights, means, variances, count: int, seed: int) -> np.ndarray:
+    """count draws (float64 [count, d]) from the Gaussian mixture with these weights, means [K,d] and diagonal
+    variances [K,d]: labels first, then the normals."""
+    rng = np.random.default_rng(seed)
+    means, variances = np.asarray(means, dtype=np.float64), np.asarray(variances, dtype=np.float64)
+    labels = rng.choice(len(weights), size=count, p=np.asarray(weights, dtype=np.float64))
+    z = rng.standard_normal((count, means.shape[1]))
+    return means[labels] + z * np.sqrt(variances[labels])
+
+
+def mixture_samples(name: str, n: int, seed: int):
+    """n fp32 samples of the mixture that config `name` draws from with seed 0 (fixed true density), the draws
+    themselves depending on `seed`; with their rule-of-thumb bandwidth.  For the known-density benchmark."""
+    w, mu, var = mixture_parameters(name, 0)
+    x = draw_from_mixture(w, mu, var, n, 7919 + seed).astype(np.float32)
+    return x, silverman_bandwidth(x)
+
+
 def standard_normal_cloud(rows: int, d: int, seed: int = 0, scale: float = 1.0) -> np.ndarray:
     """rows x d fp32 draws of N(0, scale^2), generated in fp32 chunk by chunk (for arrays too large to
     go through float64): the index-range tests use it for hundreds of millions of rows."""

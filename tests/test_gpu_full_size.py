@@ -97,3 +97,37 @@ def test_full_size_symmetric_score(name):
     print(f"{name}: symmetric vs ordinary path, all rows: rel frobenius {rel:.3g}", flush=True)
     assert rel < 1e-5
     assert torch.equal(s, P.sdkde_score(xd, h, workspace=ws, flags=flags))      # no atomics: reruns are bitwise equal
+
+
+# The chain the benchmark times (score -> shift -> KDE of the SHIFTED samples at the queries), end to end against
+# the oracle on every row and query, at the two benchmark sizes the oracle can cover completely (about 2e9 and
+# 3e9 pairs).  At C4 and C5 the oracle cannot produce all n shifted samples, so the eval step is checked there on
+# the unshifted samples (test above) and the chain only through properties.
+@pytest.mark.parametrize("name", ["C2", "C3"])
+def test_full_size_whole_pipeline_matches_oracle(name):
+    import torch
+    import paper_2602_10378_amd as P
+    from parity import assert_shifted_close
+    print(f"full-size pipeline {name}", flush=True)
+    x, q, h = sdkde_inputs.make(name, seed=0)
+    n, d = x.shape
+    m = q.shape[0]
+    s_ref, x_sd_ref, logp_ref = oracle.sd_kde_log_density(x, q, h)
+    print(f"{name}: oracle done", flush=True)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ws = P.make_workspace(n, m, d)
+    s = P.sdkde_score(xd, h, workspace=ws)
+    x_sd = P.sdkde_debias(xd, s, h)
+    dens, logd = P.sdkde_eval(x_sd, qd, h, want="both", workspace=ws)
+    worst, frob = assert_score_close(s.cpu().numpy(), s_ref, f"{name} score")
+    e_sd = assert_shifted_close(x_sd.cpu().numpy(), x_sd_ref, s_ref, h, f"{name} shifted samples")
+    e_log = assert_log_density_close(logd.cpu().numpy(), logp_ref, f"{name} SD-KDE")
+    e_den = assert_density_close(dens.cpu().numpy(), logp_ref, f"{name} SD-KDE")
+    print(f"{name}: all {n} rows / {m} queries: score worst {worst:.3g} of allowance (rel frobenius {frob:.3g}), shifted "
+          f"samples {e_sd:.3g} of allowance, log density err {e_log:.3g}, density rel err {e_den:.3g}", flush=True)
+    # the one-call entry point gives the same chain
+    s2 = torch.empty_like(xd)
+    x_sd2, dens2, logd2 = P.sdkde_fit_eval(xd, qd, h, score_out=s2, want="both", workspace=ws)
+    assert torch.equal(s2, s)
+    assert_log_density_close(logd2.cpu().numpy(), logp_ref, f"{name} SD-KDE, one call")
+    assert_density_close(dens2.cpu().numpy(), logp_ref, f"{name} SD-KDE, one call")
