@@ -123,34 +123,42 @@ class Workload:
             r["launch_ms"] = ms
             r["kernel"] = ("pair_thin_kernel" if thin else "pair_sym_kernel + in-block pass" if (eff == "symmetric" and stage == "score")
                            else "pair_lds_kernel" if (stage == "eval" and plan["dp"] >= 64 and eff == "fp32") else "pair_mfma_kernel") + f" ({stage})"
-            r["ceiling"] = self.mix_ceiling(stage, eff, thin)
+            r["ceiling"] = self.mix_ceiling(stage, "fp32" if (stage == "eval" and eff == "symmetric") else eff, thin, ms, pairs,
+                                            max(r["seconds_at_peak"].values()))
             out[key] = r
         return out, plan_s
 
-    def mix_ceiling(self, stage, mode, thin):
-        """Share of the bound's peak that this kernel's instruction mix can reach on gfx950, where fp32 MFMA and
-        vector work do not overlap on a SIMD: from the clocks sdkde_peaks measures (profiles/peaks_*.txt)."""
+    def mix_ceiling(self, stage, mode, thin, ms, pairs, at_peak_s):
+        """What this kernel's instruction mix can reach on gfx950, where fp32 MFMA and vector work do not overlap
+        on a SIMD: SIMD clocks per 256 pairs (nominal 2.4 GHz, 1024 SIMDs) of the kernel as timed, of its mix as
+        sdkde_peaks measures it (profiles/peaks_mfma_valu_coissue.txt), and of the bound resource alone at its
+        published peak; frac = the last over the second = the share of the peak the mix allows."""
         d = self.d
+        to_clk = lambda seconds: seconds * 1024 * 2.4e9 / (pairs / 256.0)
+        out = {"kernel_clk_per_256_pairs": to_clk(ms * 1e-3), "resource_clk_per_256_pairs_at_peak": to_clk(at_peak_s),
+               "mix_clk_per_256_pairs": None, "frac": None}
+        blocks = -(-d // 16)
         if thin:
             plain = (3 * d + 1) if stage == "score" else (2 * d + 1)
-            return {"frac": (8.0 + 2.0 * plain) / (8.1 + 3.05 * plain),
-                    "basis": "one v_exp_f32 (8.1 clk, overlaps nothing) + plain instructions at the measured 3.05 clk next to "
-                             "exps, against 8 + 2 per plain instruction at the published rates"}
-        blocks = -(-d // 16)
-        if mode == "fp32":
-            mfma = 32.0 * (8 if stage == "score" else 4) * blocks
-            return {"frac": (mfma * d / (16.0 * blocks)) / (mfma + 4 * 8 + 8 * 4 + (13 if stage == "score" else 6)),
-                    "basis": "per 16x16 tile: the MFMAs at 32 clk each, then 4 v_exp_f32 (8 clk) + 8 v_add_f32 (4 clk) that "
-                             "cannot overlap them, + 6-13 clk of switching (measured: 333 clk for the d = 16 score mix)"}
-        if mode == "symmetric":
-            return {"frac": 384.0 / 531.0 if blocks == 1 else None,
-                    "basis": "per tile of unordered pairs at d = 16: 12 MFMAs (384 clk) of 531 clk: + exp, row and column sums, "
-                             "the transpose through LDS and the fold of T_J"}
-        if mode == "fp16x2_all" and stage == "score":
-            return {"frac": 64.0 / 147.0 if blocks == 1 else None,
-                    "basis": "per tile at d = 16: 4 fp16 MFMAs (64 clk at the 2.5 PFLOP/s peak) of the 147 clk sdkde_peaks "
-                             "measures for 4 MFMAs + 4 exp + 16 plain instructions at two waves per SIMD"}
-        return {"frac": None, "basis": "mix not measured on its own"}
+            out["mix_clk_per_256_pairs"] = 4 * (8.1 + 3.05 * plain)
+            out["basis"] = ("per pair and lane one v_exp_f32 (8.1 clk per wave instruction, overlaps nothing) and the plain "
+                            "instructions at the 3.05 clk measured next to exps (2 at the published rate)")
+        elif mode == "fp32":
+            out["mix_clk_per_256_pairs"] = 32.0 * (8 if stage == "score" else 4) * blocks + 4 * 8 + 8 * 4 + (13 if stage == "score" else 6)
+            out["basis"] = ("per 16x16 tile: the MFMAs at 32 clk each, then 4 v_exp_f32 (8 clk) + 8 v_add_f32 (4 clk) that cannot "
+                            "overlap them, + 6-13 clk of switching (measured: 333 clk for the d = 16 score mix, 206 for eval)")
+        elif blocks == 1:
+            measured = {("symmetric", "score"): (265.5, "12 MFMAs + exp, row and column sums, LDS transpose and fold per tile of unordered "
+                                                         "pairs: 531 clk per 512 ordered pairs (kernel breakdown, not a micro-benchmark)"),
+                        ("fp16x2", "score"): (226.0, "2 fp16 + 4 fp32 MFMAs + 4 exp + 8 add: 226-250 clk"),
+                        ("fp16x2", "eval"): (92.0, "2 fp16 MFMAs + 4 exp + 8 add: 92-108 clk"),
+                        ("fp16x2_all", "score"): (139.0, "4 fp16 MFMAs + 4 exp + 16 plain instructions: 139-147 clk")}
+            key = (mode if stage == "score" else "fp16x2", stage)
+            if key in measured:
+                out["mix_clk_per_256_pairs"], out["basis"] = measured[key]
+        if out["mix_clk_per_256_pairs"]:
+            out["frac"] = out["resource_clk_per_256_pairs_at_peak"] / out["mix_clk_per_256_pairs"]
+        return out
 
     def run(self, steps, warmup, fn=None, mode="fp32"):
         flags = MODE_FLAGS[mode]

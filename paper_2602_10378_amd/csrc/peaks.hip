@@ -141,39 +141,9 @@ __global__ __launch_bounds__(kBlock) void exp_order_kernel(float* out, int iters
     out[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
-// Two waves per SIMD, 8 MFMAs then 4 exps and 8 adds as one clump: either two workgroups of 256 threads per compute
-// unit (the waves of a SIMD drift freely) or one of 512 whose barrier brings the two waves of every SIMD to their
-// VALU clumps together (BARRIER).
-template <int BLOCK, bool BARRIER>
-__global__ __launch_bounds__(BLOCK) void mix_aligned_kernel(float* out, int iters, float a, float b)
-{
-    f32x4 acc[4];
-    float e[8], s[8];
-    for (int c = 0; c < 4; ++c) acc[c] = f32x4{0, 0, 0, 0};
-    for (int c = 0; c < 8; ++c) {
-        e[c] = -0.001f * (threadIdx.x + c);
-        s[c] = c;
-    }
-    for (int i = 0; i < iters; ++i) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[k % 4], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (BARRIER) __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(e[q]);
-#pragma unroll
-        for (int q = 0; q < 8; ++q) s[q] = s[q] + a;
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    float r = 0;
-    for (int c = 0; c < 4; ++c) r += acc[c].x + acc[c].y + acc[c].z + acc[c].w;
-    for (int c = 0; c < 8; ++c) r += e[c] + s[c];
-    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
-}
-
-// fp16 MFMAs: K32 ? v_mfma_f32_16x16x32_f16 : v_mfma_f32_16x16x16_f16; NM of them, then NE exps and NA adds as one clump.
-template <bool K32, int NM, int NE, int NA>
+// fp16 MFMAs: K32 ? v_mfma_f32_16x16x32_f16 : v_mfma_f32_16x16x16_f16; NM of them and NF fp32 MFMAs (16x16x4), then NE
+// exps and NA adds as one clump.
+template <bool K32, int NM, int NE, int NA, int NF = 0>
 __global__ __launch_bounds__(kBlock) void mix_f16_kernel(float* out, int iters, float a, float b)
 {
     f32x4 acc[4];
@@ -192,6 +162,8 @@ __global__ __launch_bounds__(kBlock) void mix_f16_kernel(float* out, int iters, 
             if (K32) acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a8, a8, acc[k % 4], 0, 0, 0);
             else acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x16f16(a4, a4, acc[k % 4], 0, 0, 0);
         }
+#pragma unroll
+        for (int k = 0; k < NF; ++k) acc[k % 4] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[k % 4], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int q = 0; q < NE; ++q) e[q % 8] = __builtin_amdgcn_exp2f(e[q % 8]);
@@ -234,16 +206,55 @@ void run_mix(int waves_per_simd)
            NE, NA, SPREAD ? "interleaved" : "one clump", waves_per_simd, clk, tflops);
 }
 
-template <bool K32, int NM, int NE, int NA>
+template <bool K32, int NM, int NE, int NA, int NF = 0>
 void run_mix_f16(int waves_per_simd)
 {
     const int blocks = kCUs * waves_per_simd;
     float ms = time_ms([&] {
-        hipLaunchKernelGGL((mix_f16_kernel<K32, NM, NE, NA>), dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 1.0f, 0.5f);
+        hipLaunchKernelGGL((mix_f16_kernel<K32, NM, NE, NA, NF>), dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 1.0f, 0.5f);
     });
     const double clk = ms * 1e-3 * kClockHz / kIters / waves_per_simd;
-    printf("  %d x %s + %2d exp + %2d add, one clump, %d waves/SIMD: %6.1f clk per iteration per wave\n", NM,
-           K32 ? "16x16x32_f16" : "16x16x16_f16", NE, NA, waves_per_simd, clk);
+    printf("  %d x %s + %d x 16x16x4_f32 + %2d exp + %2d add, one clump, %d waves/SIMD: %6.1f clk per iteration per wave\n", NM,
+           K32 ? "16x16x32_f16" : "16x16x16_f16", NF, NE, NA, waves_per_simd, clk);
+}
+
+// NM x v_mfma_f32_32x32x2_f32, then NE exps and NA adds as one clump.
+template <int NM, int NE, int NA>
+__global__ __launch_bounds__(kBlock) void mix32_kernel(float* out, int iters, float a, float b)
+{
+    f32x16 acc[2];
+    float e[16], s[16];
+    for (int c = 0; c < 2; ++c)
+        for (int v = 0; v < 16; ++v) acc[c][v] = 0.0f;
+    for (int c = 0; c < 16; ++c) {
+        e[c] = -0.001f * (threadIdx.x + c);
+        s[c] = c;
+    }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int k = 0; k < NM; ++k) acc[k % 2] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[k % 2], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int q = 0; q < NE; ++q) e[q % 16] = __builtin_amdgcn_exp2f(e[q % 16]);
+#pragma unroll
+        for (int q = 0; q < NA; ++q) s[q % 16] = s[q % 16] + a;
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    float r = 0;
+    for (int c = 0; c < 2; ++c)
+        for (int v = 0; v < 16; ++v) r += acc[c][v];
+    for (int c = 0; c < 16; ++c) r += e[c] + s[c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
+template <int NM, int NE, int NA>
+void run_mix32(int waves_per_simd)
+{
+    const int blocks = kCUs * waves_per_simd;
+    float ms = time_ms([&] { hipLaunchKernelGGL((mix32_kernel<NM, NE, NA>), dim3(blocks), dim3(kBlock), 0, 0, g_out, kIters, 1.0f, 0.5f); });
+    const double clk = ms * 1e-3 * kClockHz / kIters / waves_per_simd;
+    printf("  %d x 32x32x2_f32 + %2d exp + %2d add, one clump   %d waves/SIMD: %6.1f clk per iteration per wave\n", NM, NE, NA,
+           waves_per_simd, clk);
 }
 
 template <int WHAT>
@@ -267,15 +278,6 @@ void run_exp_order(const char* what)
         float ms = time_ms([&] { hipLaunchKernelGGL(exp_order_kernel<ORDER>, dim3(blocks), dim3(kBlock), 0, 0, g_out, iters, 0.999f, 0.001f); });
         printf("  %-22s %d waves/SIMD: %5.2f clk per (exp + 4 fma)\n", what, w, ms * 1e-3 * kClockHz / iters / w / 16);
     }
-}
-
-template <int BLOCK, bool BARRIER>
-void run_mix_aligned(const char* what)
-{
-    const int blocks = kCUs * 2 * kBlock / BLOCK;       // two waves per SIMD either way
-    float ms = time_ms([&] { hipLaunchKernelGGL((mix_aligned_kernel<BLOCK, BARRIER>), dim3(blocks), dim3(BLOCK), 0, 0, g_out, kIters, 1.0f, 0.5f); });
-    printf("  8 MFMA +  4 exp +  8 add, one clump, 2 waves/SIMD, %-40s: %6.1f clk per iteration per wave\n", what,
-           ms * 1e-3 * kClockHz / kIters / 2);
 }
 
 }  // namespace
@@ -321,10 +323,11 @@ int main()
         run_mix<8, 8, 16, false>(w);
     }
 
-    printf("do the VALU clumps of the two waves of a SIMD get cheaper when they coincide?\n");
-    run_mix_aligned<256, false>("two 256-thread workgroups per CU");
-    run_mix_aligned<512, false>("one 512-thread workgroup");
-    run_mix_aligned<512, true>("one 512-thread workgroup, barrier before");
+    printf("the eval kernels' mix by MFMA shape: per 256 pairs 4 x 16x16x4 + 4 exp + 8 add, per 1024 pairs 8 x 32x32x2 + 16 exp + 32 add:\n");
+    for (int w : {2, 4}) {
+        run_mix<4, 4, 8, false>(w);
+        run_mix32<8, 16, 32>(w);
+    }
 
     printf("fp16 MFMA and VALU on one SIMD (the 16x16x16 and 16x16x32 forms take the same time per instruction):\n");
     for (int w : {2, 4}) {
@@ -333,6 +336,8 @@ int main()
         run_mix_f16<true, 0, 8, 8>(w);
         run_mix_f16<true, 4, 8, 8>(w);
         run_mix_f16<true, 4, 4, 16>(w);
+        run_mix_f16<true, 2, 4, 8, 4>(w);        // the fp16x2 input mode's score mix: cross term on fp16, Phi X on fp32 MFMAs
+        run_mix_f16<true, 2, 4, 8>(w);           // its eval mix
     }
     return 0;
 }
