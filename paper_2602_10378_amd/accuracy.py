@@ -1,5 +1,5 @@
-"""Integrated-error comparison of the estimators the paper studies (Results section, "oracle density
-benchmark": MISE / MIAE of KDE, Laplace-corrected KDE and SD-KDE against a known mixture density, with the
+"""Integrated-error comparison of the estimators the paper studies (Results section, the benchmark
+against a known density: MISE / MIAE of KDE, Laplace-corrected KDE and SD-KDE against a known mixture density, with the
 negative mass of the signed Laplace estimate logged separately), run through the GPU library.
 
 With evaluation points q_k drawn from a proposal density g, every integral is a plain average:
