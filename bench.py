@@ -24,11 +24,13 @@ if ROOT not in sys.path:
 # The paper's two timed shapes (one RTX A6000, TF32 dots), keyed by (config, n, m): seconds end to end.
 PAPER_SECONDS = {("C5", 1048576, 131072): 2.3,        # abstract / conclusion
                  ("C2", 32768, 4096): 2.11e-3}        # runtime table of the Results section (--config C2 --m 4096)
-MODE_FLAGS = {"fp32": 0, "fp16x2": 1, "fp16x2_all": 2, "symmetric": 32}
+MODE_FLAGS = {"fp32": 0, "fp16x2": 1, "fp16x2_all": 2, "fp16x2_phi16": 3, "symmetric": 32}
 MODE_NOTES = {
     "fp16x2": "cross-term inputs split into fp16 hi+lo on the fp16 matrix units, fp32 accumulate; Phi X fp32",
     "fp16x2_all": "both contractions on the fp16 matrix units (inputs and Phi split into fp16 hi+lo), fp32 accumulate, "
                   "exp and row sums fp32",
+    "fp16x2_phi16": "cross-term inputs as fp16 hi+lo, Phi X on the fp16 matrix units with every weight rounded to one fp16 value "
+                    "(the row sums take the same rounded weights); fp32 accumulate, exp fp32: the least precise mode",
     "symmetric": "fp32 path; the score computes each unordered pair of samples once (phi_ij = phi_ji) and is still "
                  "counted as n^2 pairs, as the paper counts them"}
 
@@ -115,6 +117,8 @@ class Workload:
             eff = "fp32"
         if mode == "fp16x2_all" and plan_s["xt_scale"] != 2:
             eff = "fp16x2"
+        if mode == "fp16x2_phi16" and plan_s["dp"] != 16:
+            eff = "fp16x2"
         out = {}
         for key, stage, ms, plan, pairs in (("roofline", "score", score_ms, plan_s, float(n) * n),
                                             ("roofline_eval_kernel", "eval", eval_ms, plan_e, float(m) * n)):
@@ -154,6 +158,7 @@ class Workload:
                         ("fp16x2", "eval"): (92.0, "2 fp16 MFMAs + 4 exp + 8 add: 92-108 clk"),
                         ("fp16x2_all", "score"): (139.0, "4 fp16 MFMAs + 4 exp + 16 plain instructions: 139-147 clk")}
             key = (mode if stage == "score" else "fp16x2", stage)
+            measured[("fp16x2_phi16", "score")] = (None, "3 fp16 MFMAs + 4 exp + 4 add + 2 cvt + 2 dot2 + 2 mov: not measured on its own")
             if key in measured:
                 out["mix_clk_per_256_pairs"], out["basis"] = measured[key]
         if out["mix_clk_per_256_pairs"]:
@@ -266,6 +271,7 @@ def main():
             modes = ["fp16x2"]
             if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_PREC_FP16X2_ALL)["xt_scale"] == 2:      # else it runs as fp16x2 (d > 16)
                 modes.append("fp16x2_all")
+                modes.append("fp16x2_phi16")
             if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_FLAG_SYMMETRIC)["symmetric"]:
                 modes.append("symmetric")
             for mode in modes:

@@ -79,6 +79,13 @@ enum {
                                weights under ~1e-7) has scores that small.  A score at separate points
                                without the shift, calls without a Phi X contraction (eval), and d > 16
                                (where it is no faster than FP16X2) run as FP16X2. */
+    SDKDE_PREC_FP16X2_PHI16 = 3, /* as FP16X2 for the cross term, and Phi X on the fp16 matrix units with every weight
+                               rounded to ONE fp16 value (scaled by 2^14, X still hi + lo): the least precise input mode.
+                               The row sums D are taken of the same rounded weights, so T - p D is exactly the direct-form
+                               numerator sum_j fp16(phi_j) (x_j - p): the error is relative to the weights (2^-11 per
+                               term, a few 1e-4 of the score of a point at worst), not to the size of the coordinates;
+                               fp32 accumulate, exp fp32.  Applies where FP16X2_ALL applies, and runs as FP16X2
+                               elsewhere. */
     /* flags bit 4: two-pass, max-shifted sums for sdkde_eval, sdkde_eval_laplace and sdkde_score at
        separate points: a first pass finds max_j of the exponent for every point, the second sums
        phi_j / max phi, and the logarithm (or the signed density) gets the shift back.  Results then stay

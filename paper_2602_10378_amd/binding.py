@@ -17,6 +17,7 @@ SDKDE_OK = 0
 SDKDE_PREC_FP32 = 0
 SDKDE_PREC_FP16X2 = 1
 SDKDE_PREC_FP16X2_ALL = 2
+SDKDE_PREC_FP16X2_PHI16 = 3
 SDKDE_FLAG_MAX_SHIFT = 16
 SDKDE_FLAG_SYMMETRIC = 32
 SDKDE_FLAG_SAMPLES_PREPARED = 64
@@ -106,12 +107,12 @@ def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PR
 
 
 def workspace_bytes_any_precision(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) -> int:
-    """The largest of sdkde_workspace_bytes over the three precision modes, with and without the max-shifted
+    """The largest of sdkde_workspace_bytes over the precision modes, with and without the max-shifted
     sums, the other flags as given: the grid decomposition (and with it the number of partial-sum slots) depends
     on the precision mode, and the mode a score at separate points runs in depends on the shift."""
     other = flags & ~(15 | SDKDE_FLAG_MAX_SHIFT)
     return max(sdkde_workspace_bytes(n, m, d, other | prec | shift)
-               for prec in (SDKDE_PREC_FP32, SDKDE_PREC_FP16X2, SDKDE_PREC_FP16X2_ALL)
+               for prec in (SDKDE_PREC_FP32, SDKDE_PREC_FP16X2, SDKDE_PREC_FP16X2_ALL, SDKDE_PREC_FP16X2_PHI16)
                for shift in (0, SDKDE_FLAG_MAX_SHIFT))
 
 

@@ -56,7 +56,7 @@ PEAK_MFMA_F16 = 2.5e15
 PEAK_VALU_SLOTS = 256 * 4 * 32 * 2.4e9
 EXP_SLOTS = 4
 
-# stage: "score" | "eval"; mode: "fp32" | "fp16x2" | "fp16x2_all" | "symmetric"
+# stage: "score" | "eval"; mode: "fp32" | "fp16x2" | "fp16x2_all" | "fp16x2_phi16" | "symmetric"
 
 
 def pair_work(stage: str, d: int, mode: str = "fp32", thin: bool = False) -> dict:
@@ -71,11 +71,15 @@ def pair_work(stage: str, d: int, mode: str = "fp32", thin: bool = False) -> dic
     if mode == "symmetric" and score:
         # per unordered pair: Gram 2d, T_I and T_J 2d each, one exp, init + row sum + column sum adds
         return {"mfma_f32": 3.0 * d, "mfma_f16": 0.0, "exp": 0.5, "valu": 1.5}
-    if mode == "fp16x2" or (mode == "fp16x2_all" and not score):
+    if mode == "fp16x2" or (mode in ("fp16x2_all", "fp16x2_phi16") and not score):
         return {"mfma_f32": 2.0 * d if score else 0.0, "mfma_f16": 8.0 * d, "exp": 1.0, "valu": 2.0}
     if mode == "fp16x2_all":
         # both contractions on the fp16 units; six more vector instructions per four values split Phi
         return {"mfma_f32": 0.0, "mfma_f16": 16.0 * d, "exp": 1.0, "valu": 3.5}
+    if mode == "fp16x2_phi16":
+        # cross term as fp16x2 (8d), Phi X as one K = 32 MFMA per block: fp16(phi) (x_hi + x_lo) = 4d; per four values
+        # four init adds, two packed conversions, two dot products (the row sum) and two register copies
+        return {"mfma_f32": 0.0, "mfma_f16": 12.0 * d, "exp": 1.0, "valu": 2.5}
     return {"mfma_f32": (4.0 if score else 2.0) * d, "mfma_f16": 0.0, "exp": 1.0, "valu": 2.0}
 
 

@@ -57,6 +57,21 @@ __device__ __forceinline__ f16x8 split_phi(const f32x4& phi)
     return __builtin_bit_cast(f16x8, (u32x4){h01, h23, l01, l23});
 }
 
+// Single-fp16 weights (SDKDE_PREC_FP16X2_PHI16): [h(x) h(y) h(z) h(w) | the same again] with h = fp16(phi) toward zero,
+// the B operand of one K = 32 MFMA against [x_hi | x_lo]; *rowsum gets the sum of the four ROUNDED weights added
+// (v_dot2c_f32_f16 against ones: exact products, fp32 sum), so that D and T carry the same weights.
+__device__ __forceinline__ f16x8 round_phi(const f32x4& phi, float* rowsum)
+{
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const f16x2 h01 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(phi.x, phi.y));
+    const f16x2 h23 = __builtin_bit_cast(f16x2, __builtin_amdgcn_cvt_pkrtz(phi.z, phi.w));
+    const f16x2 ones = {(_Float16)1, (_Float16)1};
+    *rowsum = __builtin_amdgcn_fdot2(h23, ones, __builtin_amdgcn_fdot2(h01, ones, *rowsum, false), false);
+    const uint32_t u01 = __builtin_bit_cast(uint32_t, h01), u23 = __builtin_bit_cast(uint32_t, h23);
+    return __builtin_bit_cast(f16x8, (u32x4){u01, u23, u01, u23});
+}
+
 // Row-tile operands of one wave for NI row tiles starting at row0: -|p~|^2 and the B operand 2 * p~.
 // fp32 inputs: lane (r, g) holds coordinates 16kb + 4g .. +3 of row r (b[t][kb]).
 // fp16x2 inputs: two K = 32 operands per 16-column block, bh[t][kb][0] = [hi | hi] and
@@ -167,7 +182,8 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 
     RowTiles<KB, NI, PREC, KLAST> rows;
     rows.load(ps, pn, row0, r, g);
-    if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
+    constexpr bool SCALED = SCORE && (PREC == SDKDE_PREC_FP16X2_ALL || PREC == SDKDE_PREC_FP16X2_PHI16);
+    if (SCALED) {
         // every Phi of this kernel carries the factor 2^kPhiScaleLog2 (exact; removed from the sums at the end)
 #pragma unroll
         for (int t = 0; t < NI; ++t) rows.ni[t] += (float)kPhiScaleLog2;
@@ -202,11 +218,13 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
 
     // Operands of one sample tile, as each lane holds them.
     constexpr bool HALF2 = PREC == SDKDE_PREC_FP16X2_ALL;      // second contraction on the fp16 units too
+    constexpr bool PHI16 = PREC == SDKDE_PREC_FP16X2_PHI16;    // the same with single-fp16 weights
     struct Operands {
         f32x4 a1[KB];     // first contraction, A: the lane's 16 bytes of sample r's row, block kb (fp32: coordinates
                           // 16kb + 4g .. +3; fp16x2: elements 8g .. 8g+7 of [hi | lo])
         f32x4 a2[KT];     // second contraction, A: lane (r, g) = coordinate 16mb + r of samples 4g .. 4g+3
-                          // (fp32), or the eight halves [hi(4g..4g+3) | again] when HALF2
+                          // (fp32), the eight halves [hi(4g..4g+3) | again] when HALF2, [hi(4g..4g+3) | lo(4g..4g+3)]
+                          // when PHI16
         f32x4 a2lo[HALF2 ? KT : 1];   // HALF2 only: [lo(4g..4g+3) | again]
         f32x4 nj;         // -|x|^2 of samples 4g .. 4g+3
     };
@@ -230,6 +248,7 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
         };
         auto load_a2 = [&](int jt, Operands& o) {
             if (SCORE && !HALF2) {
+                // fp32 values, or (PHI16) hi/lo halves: 16 bytes per (column, lane group) either way
                 const float* trow = xt + ((int64_t)min(jt, t_last) * DP + r) * kTile + g * 4;
 #pragma unroll
                 for (int mb = 0; mb < KB; ++mb)
@@ -310,16 +329,24 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                         acc = fmaf(phi.z, fmaf(c.z, kLn2, lc0[t]), acc);
                         acc = fmaf(phi.w, fmaf(c.w, kLn2, lc0[t]), acc);
                         dacc[t] = acc;
-                    } else {
+                    } else if (!(SCORE && PHI16)) {
                         dacc[t] += (phi.x + phi.y) + (phi.z + phi.w);
                     }
                 }
                 c = (wrap2 ? nxt.nj : cur.nj) + nin;             // accumulator init of pair u+2
                 f16x8 bphi;
                 if (SCORE && HALF2) bphi = split_phi(phi);       // part of the same VALU clump
+                if (SCORE && PHI16) bphi = round_phi(phi, &dacc[t]);
                 __builtin_amdgcn_sched_barrier(0);
 
-                if (SCORE && !HALF2) {
+                if (SCORE && PHI16) {
+                    // one K = 32 MFMA per 16-column block: [h(4 samples) | again] against [x_hi | x_lo]
+#pragma unroll
+                    for (int mb = 0; mb < KB; ++mb)
+                        tacc[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, cur.a2[mb]), bphi,
+                                                                             tacc[t][mb], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                } else if (SCORE && !HALF2) {
 #pragma unroll
                     for (int i = 0; i < NM; ++i) {
                         const int v = i / KB, mb = i % KB;     // the KB accumulator chains interleave
@@ -404,8 +431,13 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
                     const float e = __builtin_amdgcn_exp2f(c[v]);
                     phi[v] = (own && g * 4 + v == r) ? 0.0f : e;
                 }
-                dsum[t] += (phi.x + phi.y) + (phi.z + phi.w);
-                if (!HALF2) {
+                if (!PHI16) dsum[t] += (phi.x + phi.y) + (phi.z + phi.w);
+                if (PHI16) {
+                    const f16x8 bphi = round_phi(phi, &dsum[t]);
+#pragma unroll
+                    for (int mb = 0; mb < KB; ++mb)
+                        tsum[t][mb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a2[mb]), bphi, tsum[t][mb], 0, 0, 0);
+                } else if (!HALF2) {
 #pragma unroll
                     for (int mb = 0; mb < KB; ++mb)
 #pragma unroll
@@ -422,7 +454,7 @@ __global__ __launch_bounds__(kBlock) void pair_mfma_kernel(
             }
         }
     }
-    if (SCORE && PREC == SDKDE_PREC_FP16X2_ALL) {
+    if (SCALED) {
         constexpr float unscale = 1.0f / (float)(1 << kPhiScaleLog2);
 #pragma unroll
         for (int t = 0; t < NI; ++t) {

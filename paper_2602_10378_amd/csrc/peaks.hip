@@ -338,6 +338,7 @@ int main()
         run_mix_f16<true, 4, 4, 16>(w);
         run_mix_f16<true, 2, 4, 8, 4>(w);        // the fp16x2 input mode's score mix: cross term on fp16, Phi X on fp32 MFMAs
         run_mix_f16<true, 2, 4, 8>(w);           // its eval mix
+        run_mix_f16<true, 3, 4, 10>(w);          // single-fp16-weights mode: 3 fp16 MFMAs, 4 exp, 4 add + 2 cvt + 2 dot2 + 2 mov
     }
     return 0;
 }

@@ -111,6 +111,8 @@ constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (tw
 // prec == SDKDE_PREC_FP16X2_ALL: dst_t holds fp16 pairs too, laid out as the A operand of the K = 32
 // second contraction: for tile, column c and lane group g, eight halves [hi(4g..4g+3) | the same again]
 // followed by eight halves [lo(4g..4g+3) | the same again] (twice the bytes of the fp32 layout).
+// prec == SDKDE_PREC_FP16X2_PHI16: dst_t holds, for tile, column c and lane group g, eight halves
+// [hi(4g..4g+3) | lo(4g..4g+3)].
 // Grid: job0's blocks first (blocks0 of them), then job1's.
 __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
                                                            PrepCommon common, float a, int prec, Stamp stamp)
@@ -148,7 +150,18 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
         used[rr][c] = v;
     }
     __syncthreads();
-    if (job.dst_t && prec != SDKDE_PREC_FP16X2_ALL) {
+    if (job.dst_t && prec == SDKDE_PREC_FP16X2_PHI16) {
+        // A operand of the K = 32 second contraction with single-fp16 weights: for tile, column c and lane group g,
+        // eight halves [hi(4g..4g+3) | lo(4g..4g+3)] (the bytes of the fp32 layout)
+        _Float16* base = reinterpret_cast<_Float16*>(job.dst_t) + (r0 / kTile) * (int64_t)dp * 32;
+        for (int idx = threadIdx.x; idx < kPrepRows * dp * 2; idx += kBlock) {
+            // idx = ((tile*dp + c)*4 + g)*8 + e
+            const int e = idx % 8, g = (idx / 8) % 4, c = (idx / 32) % dp, tile = idx / (32 * dp);
+            const float v = raw[tile * kTile + 4 * g + (e & 3)][c];
+            const _Float16 hi = (_Float16)v;
+            base[idx] = e < 4 ? hi : (_Float16)(v - (float)hi);
+        }
+    } else if (job.dst_t && prec != SDKDE_PREC_FP16X2_ALL) {
         float* base = job.dst_t + (r0 / kTile) * (int64_t)dp * kTile;
         for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
             const int tile = idx / (dp * kTile), c = (idx / kTile) % dp, rr = idx % kTile;

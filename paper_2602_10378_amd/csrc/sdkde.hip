@@ -36,7 +36,7 @@ constexpr bool lds_staged(int kb, int prec) { return prec == SDKDE_PREC_FP32 && 
 constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
 {
     const bool second = kind == kScoreSelf || kind == kScorePoints || kind == kScoreBand;   // has the Phi X contraction
-    if (prec == SDKDE_PREC_FP16X2_ALL && kb > 1) return 0;              // see effective_prec()
+    if ((prec == SDKDE_PREC_FP16X2_ALL || prec == SDKDE_PREC_FP16X2_PHI16) && kb > 1) return 0;      // see effective_prec()
     if (kind == kScoreBand && (kb > 2 || prec != SDKDE_PREC_FP32)) return 0;          // see sym_row_tiles()
     if (!second && lds_staged(kb, prec)) return 4;
     return second ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
@@ -58,7 +58,7 @@ inline uint32_t effective_prec(uint32_t flags, bool thin, int dp)
 {
     const uint32_t prec = flags & 15u;
     if (thin) return SDKDE_PREC_FP32;
-    if (prec == SDKDE_PREC_FP16X2_ALL && dp > 16) return SDKDE_PREC_FP16X2;
+    if ((prec == SDKDE_PREC_FP16X2_ALL || prec == SDKDE_PREC_FP16X2_PHI16) && dp > 16) return SDKDE_PREC_FP16X2;
     return prec;
 }
 
@@ -68,7 +68,8 @@ inline uint32_t effective_prec(uint32_t flags, bool thin, int dp)
 // whose weights are all below ~1e-7 would lose them in T but not in D), so it runs the fp16x2 mode instead.
 inline uint32_t anchored_flags(uint32_t flags, bool self)
 {
-    if ((flags & 15u) == SDKDE_PREC_FP16X2_ALL && !self && !(flags & SDKDE_FLAG_MAX_SHIFT))
+    const uint32_t prec = flags & 15u;
+    if ((prec == SDKDE_PREC_FP16X2_ALL || prec == SDKDE_PREC_FP16X2_PHI16) && !self && !(flags & SDKDE_FLAG_MAX_SHIFT))
         return (flags & ~15u) | SDKDE_PREC_FP16X2;
     return flags;
 }
@@ -115,7 +116,7 @@ double row_tiles_penalty(bool score, int kb, int ni, uint32_t prec)
         // 2 / 4 / 8 row tiles 6.51 / 6.02 / 6.13 ms, d = 32 2 / 4: 12.1 / 10.7, d = 64: 24.0 / 21.7; fp16x2-all
         // (d = 16 only): 9.88 / 5.25 / 4.36 ms.  Eval: d = 16 2 / 4 / 8 / 16: 3.01 / 2.41 / 2.27 / 2.95 ms,
         // d = 32 2 / 4 / 8: 8.15 / 4.30 / 3.39, d = 64 2 / 4: 15.3 / 7.9 ms.
-        if (score && prec == SDKDE_PREC_FP16X2_ALL) return ni >= 8 ? 1.0 : ni == 4 ? 1.2 : 2.25;
+        if (score && (prec == SDKDE_PREC_FP16X2_ALL || prec == SDKDE_PREC_FP16X2_PHI16)) return ni >= 8 ? 1.0 : ni == 4 ? 1.2 : 2.25;
         if (score) return kb >= 5 ? 1.0 : kb == 1 ? (ni >= 8 ? 1.018 : ni == 4 ? 1.0 : 1.08) : (ni >= 4 ? 1.0 : 1.12);
         if (kb == 1) return ni == 16 ? 1.32 : ni == 8 ? 1.0 : ni == 4 ? 1.065 : 1.33;
         if (kb == 2) return ni == 8 ? 1.0 : ni == 4 ? 1.27 : 2.4;
@@ -153,6 +154,7 @@ double plan_cost(bool score, int kb, uint32_t prec, int64_t m, int64_t m_pad, in
     double tile_clk = 33.0 * (score ? 8 : 4) * kb + 50.0;
     if (prec == SDKDE_PREC_FP16X2) tile_clk *= 0.62;
     if (prec == SDKDE_PREC_FP16X2_ALL) tile_clk *= score ? 0.41 : 0.62;
+    if (prec == SDKDE_PREC_FP16X2_PHI16) tile_clk *= score ? 0.36 : 0.62;
     const double slot_bytes = (double)m_pad * (score ? 16 * kb + 1 : 1) * 8.0;
     const double slot = slot_bytes / 1250.0 / tile_clk;          // 1250 bytes per clock = 3 TB/s at 2.4 GHz
     return work + tail + nsplit * slot;
@@ -532,6 +534,7 @@ int launch_pair_prec(const Plan& p, const Workspace& w, uint32_t flags, const fl
     constexpr bool has_second = KIND == kScoreSelf || KIND == kScorePoints || KIND == kScoreBand;
     if constexpr (has_second) {
         if (prec == SDKDE_PREC_FP16X2_ALL) return launch_pair<KIND, SDKDE_PREC_FP16X2_ALL>(p, w, shift, st);
+        if (prec == SDKDE_PREC_FP16X2_PHI16) return launch_pair<KIND, SDKDE_PREC_FP16X2_PHI16>(p, w, shift, st);
     }
     // kinds without a second contraction: the two fp16 modes are the same kernel
     if (prec != SDKDE_PREC_FP32) return launch_pair<KIND, SDKDE_PREC_FP16X2>(p, w, shift, st);
@@ -674,7 +677,7 @@ int check_common(const void* samples, int64_t n, int64_t m, int32_t d, double h,
 {
     if (!samples || n < 1 || m < 0 || d < 1 || bad_bandwidth(h)) return SDKDE_EINVAL;
     constexpr uint32_t known = 15u | SDKDE_FLAG_MAX_SHIFT | SDKDE_FLAG_SYMMETRIC | SDKDE_FLAG_SAMPLES_PREPARED;
-    if (d > SDKDE_MAX_D || (flags & ~known) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_ALL) return SDKDE_EUNSUPPORTED;
+    if (d > SDKDE_MAX_D || (flags & ~known) != 0 || (flags & 15u) > SDKDE_PREC_FP16X2_PHI16) return SDKDE_EUNSUPPORTED;
     if (n > (int64_t)1 << 34 || m > (int64_t)1 << 34) return SDKDE_EUNSUPPORTED;
     return SDKDE_OK;
 }

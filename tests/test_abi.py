@@ -51,7 +51,7 @@ def test_workspace_bytes_scales_and_validates():
     with pytest.raises(P.SdkdeError) as e:
         P.sdkde_workspace_bytes(10, 1, 129)
     assert e.value.status == 2
-    for bad_flags in (7, 128, 16 | 3, 32 | 3):
+    for bad_flags in (7, 128, 16 | 4, 32 | 5):
         with pytest.raises(P.SdkdeError) as e:
             P.sdkde_workspace_bytes(10, 1, 16, flags=bad_flags)
         assert e.value.status == 2

@@ -52,7 +52,8 @@ def test_full_size_sampled_parity(name):
     print(f"{name}: eval on {len(qrows)} queries: log err {e_log:.3g}, density rel err {e_den:.3g}", flush=True)
 
     # fp16x2 input modes on the same sampled rows (reported separately)
-    for label, flags in (("fp16x2", P.SDKDE_PREC_FP16X2), ("fp16x2-all", P.SDKDE_PREC_FP16X2_ALL)):
+    for label, flags in (("fp16x2", P.SDKDE_PREC_FP16X2), ("fp16x2-all", P.SDKDE_PREC_FP16X2_ALL),
+                         ("fp16x2-phi16", P.SDKDE_PREC_FP16X2_PHI16)):
         s16 = P.sdkde_score(xd, h, workspace=ws, flags=flags)
         worst16, frob16 = assert_score_close(s16[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref, f"{name} score {label}")
         _, logd16 = P.sdkde_eval(xd, qd, h, want="log", workspace=ws, flags=flags)

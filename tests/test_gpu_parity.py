@@ -146,12 +146,12 @@ def test_eval_kinds_at_large_dimension(lib, d, row_tiles, tuning):
     assert_score_close(sp, oracle.score(x, h, points=q), f"large-d shifted score d={d}")
 
 
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 3])
 @pytest.mark.parametrize("n,m,d,seed", [(4096, 1024, 16, 0), (1000, 333, 16, 1), (1200, 200, 5, 6), (1100, 130, 20, 7),
                                         (2048, 512, 64, 10), (700, 90, 100, 11), (17, 9, 16, 2), (3000, 500, 1, 0)])
 def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed, mode):
     P, torch = lib
-    flags = {1: P.SDKDE_PREC_FP16X2, 2: P.SDKDE_PREC_FP16X2_ALL}[mode]
+    flags = {1: P.SDKDE_PREC_FP16X2, 2: P.SDKDE_PREC_FP16X2_ALL, 3: P.SDKDE_PREC_FP16X2_PHI16}[mode]
     print(f"fp16x2 mode {mode} n={n} m={m} d={d}", flush=True)
     x, q, h = _mixture(n, m, d, seed)
     xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
@@ -176,7 +176,7 @@ def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed, mode):
 # Phi runs out of range.  The library uses that split only next to a weight of one (header, the
 # FP16X2_ALL mode); the score at separate points must hold the plain tolerance in every mode, the score
 # at the samples the tolerance plus the absolute term the header states.
-@pytest.mark.parametrize("flags", [0, 1, 2, 18])
+@pytest.mark.parametrize("flags", [0, 1, 2, 18, 3, 19])
 def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
     P, torch = lib
     n, m, d = 5445, 2306, 17
@@ -196,7 +196,7 @@ def test_score_with_narrow_bandwidth_in_every_mode(lib, flags):
     s_ref = oracle.score(x, h)
     ref = np.linalg.norm(s_ref, axis=1)
     allow = 1e-3 * np.maximum(ref, 1e-3 * np.sqrt(np.mean(ref**2)))
-    if (flags & 15) == 2:
+    if (flags & 15) in (2, 3):
         radius = np.linalg.norm(x - x.mean(0), axis=1).max()
         allow = allow + n * 2.0**-39 * radius / h**2
     worst_s = float(np.max(np.linalg.norm(s - s_ref, axis=1) / allow))

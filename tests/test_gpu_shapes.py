@@ -255,7 +255,7 @@ def test_default_workspace_serves_every_precision_mode():
     xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
     ws = P.make_workspace(n, m, d)
     ref = None
-    for flags in (P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_FLAG_MAX_SHIFT):
+    for flags in (P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_PREC_FP16X2_PHI16, P.SDKDE_FLAG_MAX_SHIFT):
         s = P.sdkde_score(xd, h, workspace=ws, flags=flags)
         sp = P.sdkde_score(xd, h, points=qd, workspace=ws, flags=flags)
         _, logd = P.sdkde_eval(xd, qd, h, want="log", workspace=ws, flags=flags)
@@ -287,7 +287,7 @@ def test_every_call_and_flag_accepts_the_default_workspace():
         h = 1.0 + 0.1 * d**0.5
         plain = P.make_workspace(n, m, d)
         symmetric = P.make_workspace(n, m, d, flags=P.SDKDE_FLAG_SYMMETRIC)
-        for flags in (0, 1, 2, 16, 17, 18, 32, 48):
+        for flags in (0, 1, 2, 3, 16, 17, 18, 19, 32, 48):
             ws = symmetric if flags & P.SDKDE_FLAG_SYMMETRIC else plain
             s = P.sdkde_score(x, h, workspace=ws, flags=flags)
             sp = P.sdkde_score(x, h, points=q, workspace=ws, flags=flags)

@@ -7,7 +7,7 @@ from hypothesis import given, settings, strategies as st
 
 import paper_2602_10378_amd as P
 
-FLAGS = [P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_FLAG_MAX_SHIFT,
+FLAGS = [P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_PREC_FP16X2_PHI16, P.SDKDE_FLAG_MAX_SHIFT,
          P.SDKDE_FLAG_SYMMETRIC, P.SDKDE_FLAG_SYMMETRIC | P.SDKDE_PREC_FP16X2,
          P.SDKDE_FLAG_SYMMETRIC | P.SDKDE_FLAG_MAX_SHIFT]
 
@@ -129,7 +129,7 @@ def test_one_workspace_serves_every_precision_mode(n, m, d, other):
     score at separate points on the max-shift flag, so the buffer the binding makes by default must cover the plan
     of every mode and call, with or without the shift and the symmetric flag."""
     size = max(P.workspace_bytes_any_precision(n, m, d, other), P.workspace_bytes_any_precision(n, m, d, other & ~P.SDKDE_FLAG_SYMMETRIC))
-    for prec in (P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL):
+    for prec in (P.SDKDE_PREC_FP32, P.SDKDE_PREC_FP16X2, P.SDKDE_PREC_FP16X2_ALL, P.SDKDE_PREC_FP16X2_PHI16):
         for shift in (0, P.SDKDE_FLAG_MAX_SHIFT):
             for flags in (other | prec | shift, (other & ~P.SDKDE_FLAG_SYMMETRIC) | prec | shift):
                 for call in range(3):
@@ -137,7 +137,7 @@ def test_one_workspace_serves_every_precision_mode(n, m, d, other):
 
 
 def test_describe_plan_rejects_bad_arguments():
-    for args in ((0, 1, 16, 0, 0), (10, 10, 16, 3, 0), (10, 10, 200, 0, 0), (10, 10, 16, 0, 99)):
+    for args in ((0, 1, 16, 0, 0), (10, 10, 16, 3, 0), (10, 10, 200, 0, 0), (10, 10, 16, 0, 100)):
         with pytest.raises(P.SdkdeError):
             P.sdkde_describe_plan(*args)
 
