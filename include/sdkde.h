@@ -16,8 +16,9 @@
  *    once; the pairwise arithmetic itself is fp32 (fp32 MFMA inputs, fp32 accumulation) unless
  *    `flags` selects another input mode.
  *  - Accuracy domain of the matrix path (d >= 7, and the eval calls at d >= 4): squared distances are formed as
- *    |p|^2 + |x|^2 - 2 p.x on mean-centred coordinates, which loses about (R/h)^2 * 2^-24 in
- *    the exponent of phi (R = distance of a point from the sample mean).  The stated 1e-3
+ *    |p|^2 + |x|^2 - 2 p.x on coordinates taken relative to a centre of the samples (the mean of an evenly
+ *    strided subsample of them), which loses about (R/h)^2 * 2^-24 in the exponent of phi (R = distance of a
+ *    point from that centre).  The stated 1e-3
  *    tolerances hold while R/h stays below ~100; the thin path (d <= 3, the score calls d <= 6) uses direct
  *    differences and has no such limit.  (Far outside that domain, R/h above ~1e18, the scaled
  *    coordinates overflow fp32 on either path and the outputs are NaN.)  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
@@ -104,7 +105,7 @@ enum {
     /* flags bit 6, sdkde_eval and sdkde_eval_laplace only (evaluating one fitted estimate at many batches of
        queries): the workspace still holds what the previous sdkde_eval / sdkde_eval_laplace call on it prepared
        from the same samples, n, d, h and precision mode, and nothing else has used the workspace since: the
-       column means and the prepared samples are reused and only the queries are prepared (m may differ from
+       centre and the prepared samples are reused and only the queries are prepared (m may differ from
        call to call, the workspace being large enough for each m used; at n = 2^20 this saves about 0.3 ms per call).  The samples are not read.  The workspace
        keeps a record of what was prepared (kind of call, samples pointer, n, d, h, precision mode); a call whose
        arguments do not match that record returns SDKDE_OK like any other but writes NaN to every output, so a
@@ -169,7 +170,7 @@ int sdkde_eval(const float *samples_sd, int64_t n, const float *queries, int64_t
  * The whole SD-KDE pass in one call (Method section, opening paragraph: form the empirical SD-KDE,
  * score + shift, and evaluate the resulting density on the queries): sdkde_score at the samples,
  * the shift fused into its epilogue, then sdkde_eval of the shifted samples, with the shifted samples
- * centred on the mean already computed for the samples (two launches fewer than the three calls).
+ * centred on the centre already computed for the samples (one launch fewer than the three calls).
  *   samples [n, d] in      queries [m, d] in
  *   score_out [n, d] out, may be NULL      samples_sd_out [n, d] out, required
  *   density_out / log_density_out [m] out, either may be NULL, not both (unless m = 0)
