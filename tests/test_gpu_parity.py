@@ -353,7 +353,7 @@ def test_identical_samples_have_zero_score(lib):
 
 @pytest.mark.parametrize("d", [1, 16])
 def test_translation_far_from_origin(lib, d):
-    # The library centres on the sample mean, so a large common offset must not cost accuracy
+    # The library centres on a mean of the samples, so a large common offset must not cost accuracy
     # beyond the rounding of the shifted fp32 inputs themselves.
     P, torch = lib
     x, q, h = _mixture(2000, 200, d, 31)
@@ -363,6 +363,39 @@ def test_translation_far_from_origin(lib, d):
     s_ref, _, logp_ref = oracle.sd_kde_log_density(xo, qo, h)
     assert_score_close(s, s_ref, f"offset d={d}")
     assert_log_density_close(logd, logp_ref, f"offset d={d}")
+
+
+@pytest.mark.parametrize("order", ["sorted", "periodic"])
+@pytest.mark.parametrize("d", [16, 40])
+def test_centre_of_a_strided_subsample_copes_with_ordered_samples(lib, d, order):
+    """The centre is the mean of an evenly strided subsample of the samples.  Orderings that could fool a
+    subsample must not cost accuracy: samples sorted by mixture component (a prefix would see one cluster), and
+    samples arranged so that every row the subsample picks (stride n / rows) comes from the same component, which
+    puts the centre inside one cluster instead of between them."""
+    P, torch = lib
+    n, m = 8192, 300
+    x, q, h = sdkde_inputs.gaussian_mixture(n, m, d, components=4, seed=61)
+    key = np.linalg.norm(x - x[0], axis=1)                  # the component of x[0] first, the others by distance
+    by_cluster = np.argsort(key, kind="stable")
+    if order == "sorted":
+        x = np.ascontiguousarray(x[by_cluster])
+    else:
+        rows = max(32, 4096 // d)
+        stride = n // rows
+        picked = np.arange(rows) * stride                   # the rows the subsample reads
+        rest = np.setdiff1d(np.arange(n), picked)
+        arranged = np.empty_like(x)
+        arranged[picked] = x[by_cluster[:rows]]             # all from the cluster of x[0]
+        arranged[rest] = x[by_cluster[rows:]]
+        x = arranged
+    print(f"ordered samples d={d} {order}", flush=True)
+    s, x_sd, dens, logd = _gpu_pipeline(P, torch, x, q, h)
+    s_ref, x_sd_ref, logp_ref = oracle.sd_kde_log_density(x, q, h)
+    worst, frob = assert_score_close(s, s_ref, f"{order} d={d}")
+    assert_shifted_close(x_sd, x_sd_ref, s_ref, h, f"{order} d={d}")
+    e_log = assert_log_density_close(logd, logp_ref, f"{order} d={d}")
+    print(f"ordered samples d={d} {order}: score worst {worst:.3g} of allowance (rel frobenius {frob:.3g}), log err {e_log:.3g}",
+          flush=True)
 
 
 @pytest.mark.parametrize("d", [1, 16, 64])
