@@ -35,7 +35,7 @@ MODE_NOTES = {
                  "counted as n^2 pairs, as the paper counts them"}
 
 
-def traffic_from_profile(config, plan):
+def traffic_from_profile(config, plan, launch_ms=None):
     """HBM bytes per launch of the score main kernel as the committed rocprofv3 --pmc summary of this config
     recorded them (FETCH_SIZE / WRITE_SIZE, calibrated on a plain streaming kernel), with the kernel's algorithmic
     bytes beside them: the prepared samples read once plus one partial-sum slot written per split."""
@@ -53,6 +53,8 @@ def traffic_from_profile(config, plan):
     detail = {"source": os.path.relpath(files[0], ROOT), "kernel": rec["kernel"], "read_bytes": rec["read_bytes"],
               "written_bytes": rec["written_bytes"], "algorithmic_bytes_of_the_launch": algorithmic,
               "ratio_to_algorithmic": rec["bytes"] / algorithmic,
+              "hbm_gb_per_s": (rec["bytes"] / (launch_ms * 1e-3) / 1e9) if launch_ms else None,
+              "hbm_frac_of_8_tb_per_s": (rec["bytes"] / (launch_ms * 1e-3) / 8e12) if launch_ms else None,
               "note": "re-reads of the streamed samples come from L2 misses per XCD (each XCD streams its share of the "
                       "samples once per round of resident workgroups); HBM stays non-binding"}
     return rec["bytes"], detail
@@ -158,7 +160,7 @@ class Workload:
                         ("fp16x2", "eval"): (92.0, "2 fp16 MFMAs + 4 exp + 8 add: 92-108 clk"),
                         ("fp16x2_all", "score"): (139.0, "4 fp16 MFMAs + 4 exp + 16 plain instructions: 139-147 clk")}
             key = (mode if stage == "score" else "fp16x2", stage)
-            measured[("fp16x2_phi16", "score")] = (None, "3 fp16 MFMAs + 4 exp + 4 add + 2 cvt + 2 dot2 + 2 mov: not measured on its own")
+            measured[("fp16x2_phi16", "score")] = (107.0, "3 fp16 MFMAs + 4 exp + 10 plain instructions (4 add, 2 cvt, 2 dot2, 2 mov): 107-115 clk")
             if key in measured:
                 out["mix_clk_per_256_pairs"], out["basis"] = measured[key]
         if out["mix_clk_per_256_pairs"]:
@@ -204,6 +206,7 @@ def oracle_sample(w, budget_s=15.0):
     dt = time.perf_counter() - t0
     pairs = float(len(rows)) * n + float(len(qrows)) * n
     base = {"value": pairs / dt, "unit": "pairs/s", "cores": oracle.threads(), "kind": "oracle",
+            "whole_config_seconds_extrapolated": w.pairs / (pairs / dt),
             "sample": f"{len(rows)} of {n} score rows + {len(qrows)} of {m} queries (random + tile/split-boundary rows), "
                       f"each against all {n} samples ({pairs:.3g} pairs in {dt:.1f} s, fp64)"}
     return base, {"rows": rows, "qrows": qrows, "s_ref": s_ref, "logp_ref": logp_ref}
@@ -255,7 +258,8 @@ def main():
     default_shape = args.n is None and args.m is None
     if main_run["roofline"]["bound"] == "mfma":
         main_run["roofline"]["flops_per_launch"] = main_run["roofline"]["work_per_pair"]["mfma_f32"] * float(n) * n
-    traffic, traffic_detail = traffic_from_profile(args.config, plan) if default_shape else (None, None)
+    traffic, traffic_detail = (traffic_from_profile(args.config, plan, main_run["roofline"]["launch_ms"]) if default_shape
+                               else (None, None))
     main_run["roofline"]["traffic"] = traffic
     if traffic_detail:
         main_run["roofline"]["traffic_detail"] = traffic_detail
@@ -325,7 +329,8 @@ def main():
             rec["fused_call_ms_per_step"] = fused["ms_per_step"]
             rec["fused_call_value"] = fused["value"]
             rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
-            traffic, detail = traffic_from_profile(name, plan_c) if (n_o is None and m_o is None) else (None, None)
+            traffic, detail = (traffic_from_profile(name, plan_c, rec["roofline"]["launch_ms"]) if (n_o is None and m_o is None)
+                               else (None, None))
             rec["roofline"]["traffic"] = traffic
             if detail:
                 rec["roofline"]["traffic_detail"] = detail

@@ -97,5 +97,7 @@ def roofline(stage: str, d: int, pairs: float, seconds: float, mode: str = "fp32
     return {"bound": "alu" if bound == "alu" else "mfma", "resource": bound, "achieved": work / seconds / 1e12,
             "peak": peak / 1e12, "unit": unit, "frac": work / seconds / peak, "work_per_pair": w,
             "seconds_at_peak": {k: v for k, v in t.items() if v > 0.0},
+            # the same as fractions of each roof: time the resource needs at its peak over the measured time
+            "frac_by_resource": {k: v / seconds for k, v in t.items() if v > 0.0},
             # all three resources at their peaks one after the other (no overlap at all): the other end of the range
             "frac_of_sum_of_resources": sum(t.values()) / seconds}

@@ -132,3 +132,42 @@ def test_full_size_whole_pipeline_matches_oracle(name):
     assert torch.equal(s2, s)
     assert_log_density_close(logd2.cpu().numpy(), logp_ref, f"{name} SD-KDE, one call")
     assert_density_close(dens2.cpu().numpy(), logp_ref, f"{name} SD-KDE, one call")
+
+
+# Properties that hold at any size, at the two sizes the oracle cannot cover: the momentum identity
+# sum_i D_i s(x_i) = 0 (the pair terms (x_j - x_i) phi_ij are antisymmetric; D_i is the unnormalised KDE at x_i),
+# invariance to a permutation of the samples and to a common translation, and bitwise equal reruns.
+@pytest.mark.parametrize("name", ["C4", "C5"])
+def test_full_size_invariants(name):
+    import torch
+    import paper_2602_10378_amd as P
+    print(f"full-size invariants {name}", flush=True)
+    x, q, h = sdkde_inputs.make(name, seed=0)
+    n, d = x.shape
+    xd = torch.from_numpy(x).cuda()
+    ws = P.make_workspace(n, n, d)
+    s = P.sdkde_score(xd, h, workspace=ws)
+    assert torch.equal(s, P.sdkde_score(xd, h, workspace=ws)), "rerun differs"
+
+    # momentum identity, in double on the device: weights D_i = exp(log p(x_i) - max)
+    _, logd = P.sdkde_eval(xd, xd, h, want="log", workspace=ws)
+    wgt = torch.exp((logd - logd.max()).double())
+    total = (wgt[:, None] * s.double()).sum(0)
+    scale = (wgt * s.double().norm(dim=1)).sum()
+    momentum = float(total.norm() / scale)
+    print(f"{name}: |sum_i D_i s_i| / sum_i D_i |s_i| = {momentum:.3g}", flush=True)
+    assert momentum < 1e-6
+
+    # permutation of the samples: the same scores, row for row, to rounding
+    perm = torch.from_numpy(np.random.default_rng(3).permutation(n)).cuda()
+    s_perm = P.sdkde_score(xd[perm].contiguous(), h, workspace=ws)
+    rel = float((s_perm - s[perm]).norm() / s.norm())
+    print(f"{name}: permuted samples: rel frobenius {rel:.3g}", flush=True)
+    assert rel < 1e-5
+
+    # translation by a common offset (exact in fp32 for these magnitudes up to the rounding of x + t itself)
+    shift = torch.full((d,), 64.0, device="cuda")
+    s_shift = P.sdkde_score((xd + shift).contiguous(), h, workspace=ws)
+    rel = float((s_shift - s).norm() / s.norm())
+    print(f"{name}: translated samples: rel frobenius {rel:.3g}", flush=True)
+    assert rel < 3e-5       # x + 64 costs up to 2^-18 in a coordinate: ~4e-6 of the distances that make up the score
