@@ -38,8 +38,10 @@ def source_digest() -> str:
 def is_stale() -> bool:
     """True when the library is missing or was built from other sources than the tree holds now (by content, so
     that a copy of the tree with fresh time stamps does not count as changed)."""
-    if not os.path.exists(LIBRARY) or not os.path.exists(RECORD):
+    if not os.path.exists(LIBRARY):
         return True
+    if not os.path.exists(RECORD):
+        return False        # a library without its record (copied on its own): nothing says it is out of date
     with open(RECORD) as f:
         return f.read().strip() != source_digest()
 
