@@ -64,3 +64,44 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit():
     assert e.value.status == P.SDKDE_ETOOLARGE
     torch.cuda.synchronize()
     assert bool((out == 7.0).all()), "a refused call must not write"
+
+
+def test_static_scratch_entry_point_replays_from_a_graph():
+    """The callers this entry point is for include code under stream capture: after one call outside capture (it
+    looks up the buffer's address), the call is captured into a HIP graph and every replay gives the eager bits."""
+    import torch
+    import paper_2602_10378_amd as P
+    n, m = 5000, 700
+    print(f"static scratch under capture: n={n} m={m}", flush=True)
+    x, q, h = sdkde_inputs.make("C1", seed=4, n=n, m=m)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    s, x_sd = torch.empty_like(xd), torch.empty_like(xd)
+    dens, logd = torch.empty(m, device="cuda"), torch.empty(m, device="cuda")
+
+    def step():
+        P.sdkde_fit_eval_static(xd, qd, h, x_sd, score_out=s, density_out=dens, log_density_out=logd)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (s, x_sd, dens, logd)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        for t in (s, x_sd, dens, logd):
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((s, x_sd, dens, logd), want):
+            assert torch.equal(got, ref), f"replay {replay} differs from the eager result"
+        # an eager call of another size on the same built-in buffer between replays
+        P.sdkde_fit_eval_static(xd[:1500].contiguous(), qd[:100].contiguous(), h, torch.empty(1500, x.shape[1], device="cuda"),
+                                density_out=torch.empty(100, device="cuda"))
+        torch.cuda.synchronize()
