@@ -171,6 +171,26 @@ def test_fp16x2_input_mode_matches_oracle(lib, n, m, d, seed, mode):
           f"log-density err {e_log:.3g}", flush=True)
 
 
+# The fp16 second contraction (both the hi + lo split and the single-fp16 weights) also serves the score at
+# separate points when the sums are max-shifted (largest weight 1): near points, far points (where the plain sums
+# underflow and only the shift keeps a result), several splits and a ragged tail, at a full and a partly filled block.
+@pytest.mark.parametrize("mode", [2, 3])
+@pytest.mark.parametrize("n,m,d", [(5000, 1300, 16), (2100, 700, 9)])
+def test_shifted_score_at_points_with_fp16_weights(lib, n, m, d, mode):
+    P, torch = lib
+    flags = mode | P.SDKDE_FLAG_MAX_SHIFT
+    print(f"shifted score at points, mode {mode} n={n} m={m} d={d}", flush=True)
+    x, q, h = _mixture(n, m, d, 23)
+    q[: m // 2] += np.float32(9.0 * h / np.sqrt(d))       # half of the points 9 h away from where they were drawn
+    plan = P.sdkde_describe_plan(n, m, d, 1, flags)
+    assert plan["xt_scale"] == (2 if mode == 2 else 1) and plan["dp"] == 16
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    sp = P.sdkde_score(xd, h, points=qd, flags=flags)
+    assert torch.equal(sp, P.sdkde_score(xd, h, points=qd, flags=flags))
+    worst, frob = assert_score_close(sp.cpu().numpy(), oracle.score(x, h, points=q), f"mode {mode} shifted points d={d}")
+    print(f"shifted score at points, mode {mode} d={d}: worst {worst:.3g} of allowance, rel frobenius {frob:.3g}", flush=True)
+
+
 # A bandwidth well under the rule of thumb in 17-D leaves most samples without close neighbours: the
 # weights that make up the score are then tiny (1e-7 and below), which is where a scaled fp16 split of
 # Phi runs out of range.  The library uses that split only next to a weight of one (header, the
