@@ -229,6 +229,59 @@ def parity_on_sample(w, ref, flags):
             "rows": int(len(ref["rows"])), "queries": int(len(ref["qrows"])), "tolerance": 1e-3}
 
 
+def _round(node):
+    if isinstance(node, dict):
+        return {k: _round(v) for k, v in node.items()}
+    if isinstance(node, float):
+        return float(f"{node:.5g}")
+    return node
+
+
+def _slim_roofline(r, with_clocks=False):
+    out = {k: r[k] for k in ("bound", "resource", "achieved", "peak", "unit", "frac") if k in r}
+    if "traffic" in r:
+        out["traffic"] = r["traffic"]
+    if with_clocks:
+        out["kernel_clk_per_256_pairs"] = r["ceiling"]["kernel_clk_per_256_pairs"]
+        out["mix_clk_per_256_pairs"] = r["ceiling"]["mix_clk_per_256_pairs"]
+    return out
+
+
+def _slim_run(rec, with_clocks=False):
+    out = {"ms_per_step": rec["ms_per_step"], "value": rec["value"], "score_ms": rec["stages_ms"]["score_main_kernel"],
+           "eval_ms": rec["stages_ms"]["eval_main_kernel"], "roofline": _slim_roofline(rec["roofline"], with_clocks),
+           "eval_frac": rec["roofline_eval_kernel"]["frac"]}
+    if "fused_call_ms_per_step" in rec:
+        out["fused_call_ms_per_step"] = rec["fused_call_ms_per_step"]
+    if "config" in rec:
+        out.update({k: rec["config"][k] for k in ("n", "m", "d")})
+    if "parity_on_sample" in rec:
+        ps = rec["parity_on_sample"]
+        out["err_vs_oracle"] = {k: ps[k] for k in ("score_rel_frobenius_vs_oracle", "score_worst_of_allowance",
+                                                    "max_abs_log_density_err_vs_oracle")}
+    return out
+
+
+def compact(out):
+    """The record as printed by default, a few KB: the headline entries in full (without the explanatory strings),
+    one short record per separately reported mode and per config, floats rounded to five significant digits.
+    --verbose prints everything."""
+    slim = {k: v for k, v in out.items() if k not in ("other_modes", "per_config")}
+    for key in ("roofline", "roofline_eval_kernel"):
+        r = dict(slim[key])
+        for drop in ("work_per_pair", "seconds_at_peak"):
+            r.pop(drop, None)
+        r["ceiling"] = {k: v for k, v in r["ceiling"].items() if k != "basis"}
+        if "traffic_detail" in r:
+            r["traffic_detail"] = {k: v for k, v in r["traffic_detail"].items() if k not in ("note", "kernel")}
+        slim[key] = r
+    if "other_modes" in out:
+        slim["other_modes"] = {k: _slim_run(v, with_clocks=True) for k, v in out["other_modes"].items()}
+    if "per_config" in out:
+        slim["per_config"] = {k: _slim_run(v) for k, v in out["per_config"].items()}
+    return _round(slim)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -241,6 +294,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-modes", action="store_true", help="skip the separately reported modes")
     ap.add_argument("--no-per-config", action="store_true", help="skip the block that times the other configs")
+    ap.add_argument("--verbose", action="store_true", help="keep the explanatory strings and every derived figure in the line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build is single-GPU; run with --gpus 1 (no multi-GPU path exists)")
@@ -341,7 +395,7 @@ def main():
             del wc
             torch.cuda.empty_cache()
         out["per_config"] = per
-    print(json.dumps(out))
+    print(json.dumps(out if args.verbose else compact(out), separators=(",", ":")))
 
 
 if __name__ == "__main__":
