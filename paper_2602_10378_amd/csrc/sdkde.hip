@@ -4,7 +4,7 @@
 // Notation follows the paper: c = 1/(2h^2), phi_ij = exp(-c |p_i - x_j|^2),
 // D_i = sum_j phi_ij, T_i = sum_j phi_ij x_j  (Method section: T = Phi X).
 //
-// All coordinates are centred on the sample mean and scaled by a = sqrt(c log2 e), so that
+// All coordinates are taken relative to a centre of the samples and scaled by a = sqrt(c log2 e), so that
 // the squared distance in scaled units is directly the (negated) argument of exp2:
 //     phi_ij = exp2( 2 p~_i . x~_j - |p~_i|^2 - |x~_j|^2 ).
 // The cross term is the Gram-matrix tile of the Method section, computed with fp32 MFMA;
