@@ -385,6 +385,31 @@ def test_translation_far_from_origin(lib, d):
     assert_log_density_close(logd, logp_ref, f"offset d={d}")
 
 
+# The stated accuracy domain of the matrix path: the Gram expansion on centred coordinates loses about
+# (R/h)^2 2^-24 in the exponent, R = distance from the centre, so the tolerances hold while R/h stays below ~100.
+# Two unit-covariance clusters 2R apart put every point at distance ~R from the centre between them.
+@pytest.mark.parametrize("ratio", [25.0, 50.0, 90.0])
+@pytest.mark.parametrize("flags", [0, 1])
+def test_accuracy_domain_of_the_gram_expansion(lib, ratio, flags):
+    P, torch = lib
+    n, m, d = 4000, 400, 16
+    rng = np.random.default_rng(int(ratio))
+    direction = rng.standard_normal(d)
+    direction /= np.linalg.norm(direction)
+    h = 1.1
+    side = np.where(rng.random(n + m) < 0.5, -1.0, 1.0)[:, None]
+    pts = (rng.standard_normal((n + m, d)) + side * ratio * h * direction).astype(np.float32)
+    x, q = np.ascontiguousarray(pts[:n]), np.ascontiguousarray(pts[n:])
+    print(f"accuracy domain R/h={ratio} flags={flags}", flush=True)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    s = P.sdkde_score(xd, h, flags=flags)
+    _, logd = P.sdkde_eval(xd, qd, h, want="log", flags=flags)
+    worst, frob = assert_score_close(s.cpu().numpy(), oracle.score(x, h), f"R/h={ratio}")
+    e_log = assert_log_density_close(logd.cpu().numpy(), oracle.eval_log_density(x, q, h), f"R/h={ratio}")
+    print(f"accuracy domain R/h={ratio} flags={flags}: score worst {worst:.3g} of allowance (rel frobenius {frob:.3g}), "
+          f"log-density err {e_log:.3g}", flush=True)
+
+
 @pytest.mark.parametrize("order", ["sorted", "periodic"])
 @pytest.mark.parametrize("d", [16, 40])
 def test_centre_of_a_strided_subsample_copes_with_ordered_samples(lib, d, order):
