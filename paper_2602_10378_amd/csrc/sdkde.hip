@@ -39,7 +39,8 @@ constexpr int max_row_tiles(int kb, int kind, int prec = SDKDE_PREC_FP32)
     if ((prec == SDKDE_PREC_FP16X2_ALL || prec == SDKDE_PREC_FP16X2_PHI16) && kb > 1) return 0;      // see effective_prec()
     if (kind == kScoreBand && (kb > 2 || prec != SDKDE_PREC_FP32)) return 0;          // see sym_row_tiles()
     if (!second && lds_staged(kb, prec)) return 4;
-    return second ? (kb == 1 ? 8 : kb <= 4 ? 4 : 2) : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
+    return second ? (kb == 1 ? 8 : (kb <= 4 || (kb == 5 && prec == SDKDE_PREC_FP32)) ? 4 : 2)
+                  : (kb == 1 ? 16 : kb == 2 ? 8 : kb <= 4 ? 4 : 2);
 }
 
 // Whether pair_mfma_kernel is also built with fewer MFMAs for a partly filled last 16-column block (KLAST < 4):
@@ -123,7 +124,10 @@ double row_tiles_penalty(bool score, int kb, int ni, uint32_t prec)
         return kb >= 5 ? 1.0 : ni == 4 ? 1.0 : 1.94;
     }
     if (score) {
-        if (kb >= 5) return 1.0;                              // only ni = 2 is built
+        if (kb >= 6) return 1.0;                              // only ni = 2 is built
+        // dp = 80: two row tiles leave room for two waves per SIMD, whose tile streams evict each other from the
+        // vector cache (n = 262144: 201 ms against 162 ms with four row tiles and one wave per SIMD)
+        if (kb == 5) return ni >= 4 ? 1.0 : 1.25;
         return ni >= 8 ? 1.0 : ni == 4 ? (kb == 1 ? 1.004 : 1.0) : (kb == 1 ? 1.12 : 1.15);
     }
     if (kb == 1) return ni == 16 ? 1.013 : ni == 8 ? 1.0 : ni == 4 ? 1.005 : 1.035;
@@ -504,7 +508,7 @@ int launch_pair(const Plan& p, const Workspace& w, const float* shift, hipStream
                 switch (p.ni) { SDKDE_CASE_NI(4, 4) SDKDE_CASE_NI(4, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 5:
-                switch (p.ni) { SDKDE_CASE_NI(5, 2) default: return SDKDE_EUNSUPPORTED; }
+                switch (p.ni) { SDKDE_CASE_NI(5, 4) SDKDE_CASE_NI(5, 2) default: return SDKDE_EUNSUPPORTED; }
                 break;
             case 6:
                 switch (p.ni) { SDKDE_CASE_NI(6, 2) default: return SDKDE_EUNSUPPORTED; }
