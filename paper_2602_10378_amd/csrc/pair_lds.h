@@ -95,6 +95,7 @@ __global__ __launch_bounds__(kBlock) void pair_lds_kernel(
             for (int kb = 0; kb < KB; ++kb) {
                 f32x4 a_next = a;
                 if (kb + 1 < KB) a_next = *reinterpret_cast<const f32x4*>(cur + (kb + 1) * 16);
+                __builtin_amdgcn_sched_barrier(0);      // the read stays a whole MFMA group ahead of its use
                 // the NI accumulator chains interleave: consecutive MFMAs are independent
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
@@ -102,6 +103,7 @@ __global__ __launch_bounds__(kBlock) void pair_lds_kernel(
                     for (int t = 0; t < NI; ++t)
                         c[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[v], rows.b[t][kb][v], c[t], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
                 a = a_next;
             }
 #pragma unroll
