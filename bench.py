@@ -88,6 +88,37 @@ class Workload:
         self.P.sdkde_fit_eval(self.xd, self.qd, self.h, score_out=self.s, samples_sd_out=self.x_sd, density_out=self.dens,
                               log_density_out=self.logd, workspace=self.ws, flags=flags)
 
+    def graph_replay_ms(self, steps):
+        """ms per replay of sdkde_fit_eval captured once into a HIP graph on a side stream (what a caller with a small,
+        fixed-shape problem in a loop would do: one graph launch instead of one launch per kernel); the replayed
+        outputs are checked against the eager call's bit for bit."""
+        torch = self.torch
+        self.fused_step()
+        torch.cuda.synchronize()
+        want = [t.clone() for t in (self.s, self.x_sd, self.dens, self.logd)]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            self.fused_step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                self.fused_step()
+        torch.cuda.synchronize()
+        for t in (self.s, self.x_sd, self.dens, self.logd):
+            t.fill_(float("nan"))
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        same = all(torch.equal(a, b) for a, b in zip((self.s, self.x_sd, self.dens, self.logd), want))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+        del graph
+        return ms, same
+
     def timed(self, fn, steps, warmup):
         """(seconds per step by the host clock around synchronisations, sorted per-step ms from events, main-kernel
         ms per launch of the score and of the eval call from the library's own events on the launch stream)."""
@@ -253,6 +284,8 @@ def _slim_run(rec, with_clocks=False):
            "eval_frac": rec["roofline_eval_kernel"]["frac"]}
     if "fused_call_ms_per_step" in rec:
         out["fused_call_ms_per_step"] = rec["fused_call_ms_per_step"]
+    if "fused_call_graph_replay_ms_per_step" in rec:
+        out["fused_call_graph_replay_ms_per_step"] = rec["fused_call_graph_replay_ms_per_step"]
     if "config" in rec:
         out.update({k: rec["config"][k] for k in ("n", "m", "d")})
     if "parity_on_sample" in rec:
@@ -382,6 +415,8 @@ def main():
             fused, _ = wc.run(k, 3, fn=wc.fused_step)
             rec["fused_call_ms_per_step"] = fused["ms_per_step"]
             rec["fused_call_value"] = fused["value"]
+            if est < 5e-3:                                           # launch-bound sizes: the same call replayed from a HIP graph
+                rec["fused_call_graph_replay_ms_per_step"], rec["graph_replay_bitwise_equal_to_eager"] = wc.graph_replay_ms(k)
             rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
             traffic, detail = (traffic_from_profile(name, plan_c, rec["roofline"]["launch_ms"]) if (n_o is None and m_o is None)
                                else (None, None))
