@@ -28,7 +28,7 @@ __device__ __forceinline__ void block_centre(const float* __restrict__ src, int6
     const int64_t stride = n / rows;                      // >= 1
     double acc = 0.0;
     if (rr < rows_per_iter) {
-#pragma unroll 4
+#pragma unroll 16
         for (int64_t k = rr; k < rows; k += rows_per_iter) acc += (double)src[k * stride * d + c];
     }
     red[threadIdx.x] = acc;
