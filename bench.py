@@ -243,6 +243,28 @@ def oracle_sample(w, budget_s=15.0):
     return base, {"rows": rows, "qrows": qrows, "s_ref": s_ref, "logp_ref": logp_ref}
 
 
+def oracle_whole(w):
+    """A config small enough for the oracle to run whole: the full chain (score at every sample, shift, KDE of the
+    shifted samples at every query) timed on the host cores, and the GPU pass compared with it element by element."""
+    import numpy as np
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from parity import score_error
+    t0 = time.perf_counter()
+    s_ref, _, logp_ref = oracle.sd_kde_log_density(w.x, w.q, w.h)
+    dt = time.perf_counter() - t0
+    base = {"value": w.pairs / dt, "unit": "pairs/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"the whole config: score at all {w.n} samples, shift, KDE of the shifted samples at all {w.m} "
+                      f"queries ({w.pairs:.3g} pairs in {dt:.2f} s, fp64)"}
+    w.step()
+    worst, frob = score_error(w.s.cpu().numpy(), s_ref)
+    logd = w.logd.cpu().numpy().astype(np.float64)
+    return base, {"score_worst_of_allowance": worst, "score_rel_frobenius_vs_oracle": frob,
+                  "max_abs_log_density_err_vs_oracle": float(np.max(np.abs(logd - logp_ref))),
+                  "rows": w.n, "queries": w.m, "tolerance": 1e-3,
+                  "density": "SD-KDE (of the shifted samples), whole pipeline"}
+
+
 def parity_on_sample(w, ref, flags):
     """Score of the mode on the sampled rows and KDE of the unshifted samples at the sampled queries, against the
     oracle's values: per-point worst error as a multiple of the 1e-3 allowance, and the global figures."""
@@ -291,7 +313,9 @@ def _slim_run(rec, with_clocks=False):
     if "parity_on_sample" in rec:
         ps = rec["parity_on_sample"]
         out["err_vs_oracle"] = {k: ps[k] for k in ("score_rel_frobenius_vs_oracle", "score_worst_of_allowance",
-                                                    "max_abs_log_density_err_vs_oracle")}
+                                                    "max_abs_log_density_err_vs_oracle", "rows", "queries")}
+    if "cpu_baseline" in rec:
+        out["cpu_baseline"] = {k: rec["cpu_baseline"][k] for k in ("value", "unit", "cores", "kind")}
     return out
 
 
@@ -418,6 +442,12 @@ def main():
             if est < 5e-3:                                           # launch-bound sizes: the same call replayed from a HIP graph
                 rec["fused_call_graph_replay_ms_per_step"], rec["graph_replay_bitwise_equal_to_eager"] = wc.graph_replay_ms(k)
             rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
+            if not args.no_cpu_baseline:
+                if wc.pairs <= 4e9:                                  # a few seconds of oracle time: run it whole
+                    rec["cpu_baseline"], rec["parity_on_sample"] = oracle_whole(wc)
+                else:
+                    rec["cpu_baseline"], ref_c = oracle_sample(wc, budget_s=3.0)
+                    rec["parity_on_sample"] = parity_on_sample(wc, ref_c, 0)
             traffic, detail = (traffic_from_profile(name, plan_c, rec["roofline"]["launch_ms"]) if (n_o is None and m_o is None)
                                else (None, None))
             rec["roofline"]["traffic"] = traffic
