@@ -111,31 +111,50 @@ class Workload:
             graph.replay()
         torch.cuda.synchronize()
         same = all(torch.equal(a, b) for a, b in zip((self.s, self.x_sd, self.dens, self.logd), want))
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) / steps * 1e3
+        ms = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                graph.replay()
+            torch.cuda.synchronize()
+            ms = min(ms, (time.perf_counter() - t0) / steps * 1e3)
         del graph
         return ms, same
 
     def timed(self, fn, steps, warmup):
-        """(seconds per step by the host clock around synchronisations, sorted per-step ms from events, main-kernel
-        ms per launch of the score and of the eval call from the library's own events on the launch stream)."""
+        """(seconds per step by the host clock around synchronisations, sorted per-step ms from events or None,
+        main-kernel ms per launch of the score and of the eval call from the library's own events on the launch
+        stream).  Where a step lasts milliseconds, the kernel events and one mark per step are recorded inside the
+        timed region.  Every event costs ~3 us on this machine (the next kernel waits for it): four kernel events
+        and a mark are 40 % of a C1 step, so short steps are timed with no event at all and the kernel events
+        are taken over a second pass of the same steps right after."""
         P, torch = self.P, self.torch
-        for _ in range(warmup):
+        for _ in range(warmup - 1):
             fn()
         torch.cuda.synchronize()
-        P.sdkde_profile_enable(True)
-        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
-        marks[0].record()
+        if warmup > 0:
+            fn()                              # the last warm-up step, timed alone to see how long a step is
+        torch.cuda.synchronize()
+        long_steps = (time.perf_counter() - t0 if warmup > 0 else self.pairs / 2e12) >= 5e-3
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)] if long_steps else None
+        P.sdkde_profile_enable(long_steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if long_steps:
+            marks[0].record()
         for k in range(steps):
             fn()
-            marks[k + 1].record()
+            if long_steps:
+                marks[k + 1].record()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps))
+        per_step = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(steps)) if long_steps else None
+        if not long_steps:
+            P.sdkde_profile_enable(True)
+            for _ in range(min(steps, 200)):
+                fn()
+            torch.cuda.synchronize()
         (ls, score_ms), (le, eval_ms) = P.sdkde_profile_summary(0), P.sdkde_profile_summary(1)
         P.sdkde_profile_enable(False)
         return dt / steps, per_step, score_ms / max(ls, 1), eval_ms / max(le, 1)
@@ -203,7 +222,8 @@ class Workload:
         sec, per_step, score_ms, eval_ms = self.timed(fn or (lambda: self.step(flags)), steps, warmup)
         roofs, plan = self.rooflines(score_ms, eval_ms, mode)
         out = {"ms_per_step": sec * 1e3, "value": self.pairs / sec, "unit": "pairs/s", "steps": steps,
-               "ms_per_step_min": per_step[0], "ms_per_step_median": per_step[len(per_step) // 2],
+               "ms_per_step_min": per_step[0] if per_step else None,
+               "ms_per_step_median": per_step[len(per_step) // 2] if per_step else None,
                "stages_ms": {"score_main_kernel": score_ms, "eval_main_kernel": eval_ms,
                              "everything_else": sec * 1e3 - score_ms - eval_ms}}
         out.update(roofs)
@@ -435,8 +455,13 @@ def main():
             wc = Workload(P, torch, sdkde_inputs, name, args.seed, n_o, m_o)
             est = wc.pairs / 1.5e12                                  # seconds per step, roughly
             k = int(max(3, min(200, 0.6 / max(est, 1e-6))))
-            rec, plan_c = wc.run(k, 3)
-            fused, _ = wc.run(k, 3, fn=wc.fused_step)
+            # short steps: enough warm-up for the clocks to settle (a few hundred launches), best of three runs
+            warm = int(max(3, min(3000, 0.15 / max(est, 1e-6))))
+            tries = 3 if est < 5e-3 else 1
+            runs = [wc.run(k, warm if r == 0 else 3) for r in range(tries)]
+            rec, plan_c = min(runs, key=lambda rp: rp[0]["ms_per_step"])
+            rec["ms_per_step_of_each_run"] = [r[0]["ms_per_step"] for r in runs]
+            fused = min((wc.run(k, 3, fn=wc.fused_step)[0] for _ in range(tries)), key=lambda r: r["ms_per_step"])
             rec["fused_call_ms_per_step"] = fused["ms_per_step"]
             rec["fused_call_value"] = fused["value"]
             if est < 5e-3:                                           # launch-bound sizes: the same call replayed from a HIP graph
