@@ -29,7 +29,7 @@ namespace {
 
 // Whether the kinds without a second contraction run pair_lds_kernel (sample tile staged in LDS) instead of
 // pair_mfma_kernel: fp32 inputs from dp = 64 on.  Measured (eval, n = 262144, m = 65536, best plan of each):
-// d = 32 9.44 against 9.10 ms (slower), d = 48 13.11 / 13.16, d = 64 16.79 / 17.57, d = 128 32.0 / 43.5 ms.
+// d = 32 9.42 against 9.10 ms (slower), d = 48 13.03 / 13.16, d = 64 16.37 / 17.57, d = 128 32.0 / 43.5 ms.
 constexpr bool lds_staged(int kb, int prec) { return prec == SDKDE_PREC_FP32 && kb >= 4; }
 
 // Most row tiles per wave for which the pair kernels are instantiated (larger ones would spill registers).
