@@ -326,3 +326,18 @@ def test_a_workspace_made_for_more_points_serves_fewer():
         assert torch.equal(got_s, P.sdkde_score(x, h, points=q, workspace=ws))      # still deterministic
     # the first shape is one where the preferred decomposition does not fit the shared buffer
     assert P.sdkde_describe_plan(72994, 54645, 16, 1)["workspace_bytes"] > P.sdkde_workspace_bytes(72994, 73086, 16)
+
+
+def test_sweep_module_times_the_papers_shapes():
+    """paper_2602_10378_amd.sweep (runtime and utilisation in the shapes of the paper's sweeps, n_test = n_train / 8):
+    one small shape per dimension; times are positive, the whole SD-KDE pass costs more than the KDE alone, and no
+    utilisation figure exceeds one."""
+    from paper_2602_10378_amd import sweep
+    for name, n, d in (("C1", 2048, 16), ("C3", 4096, 1)):
+        print(f"sweep module: {name} n={n}", flush=True)
+        rows = sweep.sweep(name, (n,), seeds=(0,), reps=5)
+        assert len(rows) == 1 and rows[0]["n"] == n and rows[0]["m"] == n // 8 and rows[0]["d"] == d
+        r = rows[0]
+        assert 0.0 < r["kde_ms"] < r["sd_kde_ms"] < 50.0 and r["laplace_ms"] > 0.0
+        assert 0.0 < r["share_of_bound"] < 1.0 and 0.0 < r["paper_model_utilisation"] < 1.0
+        assert "| %d | %d |" % (n, n // 8) in sweep.markdown(rows, "t")
