@@ -22,8 +22,10 @@
  *    tolerances hold while R/h stays below ~100; the thin path (d <= 3, the score calls d <= 6) uses direct
  *    differences and has no such limit.  (Far outside that domain, R/h above ~1e18, the scaled
  *    coordinates overflow fp32 on either path and the outputs are NaN.)  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
- *    is kept: a point at which every phi_j is below the fp32 range (exponent under -126 ln 2)
- *    gets the documented all-underflow results instead of a shifted sum.
+ *    is kept, and weights below the smallest normal fp32 number (2^-126) are flushed to zero: a point whose
+ *    weights phi_j sum to less than 1000 n 2^-126 (so that the flushed ones could be more than one part in a
+ *    thousand of the sum; the point is then farther than about 11.5 - 13 h from every sample, depending on n)
+ *    gets the all-underflow results documented with each call instead of a number that may be wrong.
  *  - Results are deterministic: no atomics are used, so repeated calls with the same
  *    arguments (and a workspace of at least sdkde_workspace_bytes, or of the same size) give
  *    bit-identical outputs.
@@ -136,8 +138,8 @@ int sdkde_workspace_bytes(int64_t n, int64_t m, int32_t d, uint32_t flags, size_
  *     s(p) = sum_j -(p - x_j) phi_j / (h^2 sum_j phi_j),  phi_j = exp(-|p - x_j|^2 / 2h^2),
  * evaluated at each of the m `points`.  points == NULL means "at the samples themselves"
  * (then m must equal n); the sum always runs over all n samples, so a point that is a
- * sample includes its own term.  A point so far from every sample that all phi_j underflow
- * in fp32 gets score 0.
+ * sample includes its own term.  A point so far from every sample that sum_j phi_j is below
+ * 1000 n 2^-126 (see above) gets score 0 (SDKDE_FLAG_MAX_SHIFT: a shifted sum instead).
  *   samples   [n, d] in      points [m, d] in (or NULL)      score_out [m, d] out
  * score_out must not overlap samples, points or workspace.
  */
@@ -159,7 +161,8 @@ int sdkde_debias(const float *samples, const float *score, int64_t n, int32_t d,
  *     p(q) = 1 / (n h^d (2 pi)^(d/2)) * sum_j exp(-|q - x_j|^2 / 2h^2).
  * density_out and log_density_out are [m] outputs; either may be NULL, not both.  The
  * density underflows to 0 where it is below the fp32 range (large d); the log density is
- * finite unless every term underflows in fp32 (then -inf).  m = 0 is a no-op.
+ * finite unless the sum of the weights is below 1000 n 2^-126 (see above; then -inf, density 0;
+ * SDKDE_FLAG_MAX_SHIFT evaluates such queries with a shifted sum).  m = 0 is a no-op.
  *   samples_sd [n, d] in     queries [m, d] in
  */
 int sdkde_eval(const float *samples_sd, int64_t n, const float *queries, int64_t m, int32_t d,

@@ -49,14 +49,14 @@ __device__ __forceinline__ float reduce_slots(const float* __restrict__ first, i
 // mode 1 (thin path):                   score = (N/D) * inv_ah2                (direct-form numerator)
 // mode 2 (MFMA path, at the samples):   score = (T' - p~ D') / (D' + 1) * inv_ah2
 //        where T', D' exclude the pair (i, i), whose weight is exactly 1.
-// inv_ah2 = 1 / (a h^2) undoes the coordinate scaling.  D == 0 gives 0.
+// inv_ah2 = 1 / (a h^2) undoes the coordinate scaling.  D < min_sum (least_trusted_sum of the sample count) gives 0.
 // score and x_sd are both optional outputs; x_sd = x + half_h2 * score (x: the original points, same indexing).
 // Grid: one workgroup per kBlock / PARTS elements of the [m, d] output.
 template <int PARTS>
 __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
     const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
     int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, int ps_split_half, float inv_ah2,
-    float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd)
+    float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd, float min_sum)
 {
     constexpr int kEpiOutputs = kBlock / PARTS;
     __shared__ float red[PARTS][kEpiOutputs];
@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
     float out = 0.0f;
     if (mode == 2) {
         out = fmaf(-pc, dsum, tsum) / (dsum + 1.0f) * inv_ah2;
-    } else if (dsum > 0.0f) {
+    } else if (dsum >= min_sum) {
         float ratio = tsum / dsum;
         out = (mode == 1 ? ratio : ratio - pc) * inv_ah2;
     }
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_kernel(
 __global__ __launch_bounds__(kBlock) void score_epilogue_quad_kernel(
     const float* __restrict__ part_t, const float* __restrict__ part_d, const float* __restrict__ ps,
     int nsplit, int64_t m, int64_t m_pad, int d, int dp, int mode, int ps_split_half, float inv_ah2,
-    float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd, int quad_io)
+    float* __restrict__ score, const float* __restrict__ x, float half_h2, float* __restrict__ x_sd, int quad_io,
+    float min_sum)
 {
     constexpr int PARTS = kEpiPartsFew, LANES = kBlock / PARTS;
     __shared__ f32x4 red_t[PARTS][LANES];
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_quad_kernel(
         }
         float o = 0.0f;
         if (mode == 2) o = fmaf(-pc, dsum, tsum[v]) / (dsum + 1.0f) * inv_ah2;
-        else if (dsum > 0.0f) o = (tsum[v] / dsum - pc) * inv_ah2;
+        else if (dsum >= min_sum) o = (tsum[v] / dsum - pc) * inv_ah2;
         out[v] = o;
     }
     const int64_t at = i * d + c0;
@@ -163,12 +164,12 @@ __global__ __launch_bounds__(kBlock) void score_epilogue_quad_kernel(
 
 // log p = log D + lognorm, lognorm = -log n - d log h - (d/2) log 2 pi (formed on the host in double).
 // signed != 0 (Laplace-corrected sum, which may be negative): density = sum * exp(lognorm) only.
-// shift (may be null): per-query base-2 exponent shift of the max-shifted mode.
+// shift (may be null): per-query base-2 exponent shift of the max-shifted mode.  min_sum: least_trusted_sum(n).
 // Grid: one workgroup per kBlock / PARTS queries.
 template <int PARTS>
 __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __restrict__ part_d, int nsplit,
                                                                int64_t m, int64_t m_pad, double lognorm, int is_signed,
-                                                               const float* __restrict__ shift,
+                                                               const float* __restrict__ shift, float min_sum,
                                                                float* __restrict__ density,
                                                                float* __restrict__ log_density)
 {
@@ -176,8 +177,11 @@ __global__ __launch_bounds__(kBlock) void eval_epilogue_kernel(const float* __re
     __shared__ float red[PARTS][kEpiOutputs];
     const int64_t i = (int64_t)blockIdx.x * kEpiOutputs + threadIdx.x % kEpiOutputs;
     const bool active = i < m;
-    const float dsum = reduce_slots<PARTS, false>(part_d + (active ? i : 0), m_pad, nsplit, active, red);
+    float dsum = reduce_slots<PARTS, false>(part_d + (active ? i : 0), m_pad, nsplit, active, red);
     if (!active || threadIdx.x >= kEpiOutputs) return;
+    // too close to the flush threshold of the weights: the all-underflow case (the signed sum of the Laplace-corrected
+    // estimate may be small because its terms cancel, and is left as it is)
+    if (!is_signed && dsum < min_sum) dsum = 0.0f;
     // max-shifted mode: the sums were taken of phi / 2^shift
     const double shift_ln = shift ? (double)shift[i] * 0.69314718055994530942 : 0.0;
     if (is_signed) {

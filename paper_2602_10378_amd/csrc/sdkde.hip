@@ -752,10 +752,10 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
         const int quad_io = (d % 4 == 0 && (io & 15) == 0) ? 1 : 0;
         hipLaunchKernelGGL(score_epilogue_quad_kernel, dim3((unsigned)((quads + per_wg - 1) / per_wg)), dim3(kBlock), 0, st,
                            w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp, mode, ps_halves, inv_ah2, score_out,
-                           samples, half_h2, samples_sd_out, quad_io);
+                           samples, half_h2, samples_sd_out, quad_io, least_trusted_sum(n));
     } else {
         SDKDE_LAUNCH_EPILOGUE(score_epilogue_kernel, nslots, total, st, w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d,
-                              p.dp, mode, ps_halves, inv_ah2, score_out, samples, half_h2, samples_sd_out);
+                              p.dp, mode, ps_halves, inv_ah2, score_out, samples, half_h2, samples_sd_out, least_trusted_sum(n));
     }
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
@@ -803,7 +803,7 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     if ((rc = profile_mark(1, 1, st)) != SDKDE_OK) return rc;
 
     SDKDE_LAUNCH_EPILOGUE(eval_epilogue_kernel, p.nsplit, m, st, w.part_d, p.nsplit, m, p.m_pad, lognorm, laplace ? 1 : 0,
-                          shift, density_out, log_density_out);
+                          shift, least_trusted_sum(n), density_out, log_density_out);
     return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
 }
 

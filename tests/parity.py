@@ -63,12 +63,34 @@ def assert_shifted_close(x_sd_gpu, x_sd_ref, s_ref, h, what=""):
     return worst
 
 
-def assert_laplace_close(p_gpu, p_ref, p_abs_ref, what=""):
-    """Signed Laplace-corrected density: |error| <= 1e-3 * max(|p_ref|, 1e-3 * p_abs_ref), where
-    p_abs_ref sums the magnitudes of the terms that cancel in p_ref."""
+def gram_exponent_error(x, q, h, low_precision_inputs=False):
+    """Bound, per query, on the absolute error of the exponent -|q - x_j|^2 / 2h^2 (in nats) as the matrix path
+    forms it in fp32: |q~|^2 + |x~|^2 - 2 q~.x~ on coordinates relative to a centre c of the samples.  With
+    E = (|q - c|^2 + max_j |x_j - c|^2) / 2h^2 the size of the terms that cancel, the stored norms are rounded once
+    each, their sum once, and each of the d/4 MFMA steps rounds an accumulator of at most that size:
+    (2 + d/4) half-ulps of E, i.e. (2 + d/4) E 2^-24.  The fp16 hi + lo input modes drop the lo.lo products,
+    2^-22 of |q~||x~| <= E per pair: four more units.  The thin path (d <= 3) forms differences directly: 0."""
+    x = np.asarray(x, dtype=np.float64)
+    q = np.asarray(q, dtype=np.float64)
+    d = x.shape[1]
+    if d <= 3:
+        return np.zeros(q.shape[0])
+    c = x.mean(axis=0)
+    big = ((q - c) ** 2).sum(axis=1) + float(((x - c) ** 2).sum(axis=1).max())
+    return (2.0 + d / 4.0 + (4.0 if low_precision_inputs else 0.0)) * big / (2.0 * h * h) * 2.0**-24
+
+
+def assert_laplace_close(p_gpu, p_ref, p_abs_ref, what="", exponent_error=None, p_kde_ref=None):
+    """Signed Laplace-corrected density: |error| <= max(1e-3 |p_ref|, 1e-6 p_abs_ref, e (p_abs_ref + p_kde_ref)),
+    where p_abs_ref sums the magnitudes of the terms that cancel in p_ref and e = exponent_error (per query,
+    gram_exponent_error) is what the fp32 Gram expansion can lose in every term's exponent: a term
+    phi (1 + d/2 - u) with u off by e changes by at most e (|1 + d/2 - u| + 1) phi, which sums to
+    e (p_abs_ref + p_kde_ref) over the samples (p_kde_ref: the plain KDE at the same queries)."""
     p_gpu = np.asarray(p_gpu, dtype=np.float64)
     big = p_abs_ref >= 1e-30
-    allow = TOL * np.maximum(np.abs(p_ref[big]), 1e-3 * p_abs_ref[big])
-    worst = float(np.max(np.abs(p_gpu[big] - p_ref[big]) / allow)) if big.any() else 0.0
+    allow = np.maximum(TOL * np.abs(p_ref), TOL * 1e-3 * p_abs_ref)
+    if exponent_error is not None:
+        allow = np.maximum(allow, exponent_error * (p_abs_ref + p_kde_ref))
+    worst = float(np.max(np.abs(p_gpu[big] - p_ref[big]) / allow[big])) if big.any() else 0.0
     assert worst <= 1.0, f"{what}: Laplace density error {worst:.3g}x the allowance"
     return worst

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import sdkde_inputs
-from parity import (assert_density_close, assert_laplace_close, assert_log_density_close, assert_score_close,
+from parity import (TOL, gram_exponent_error, assert_density_close, assert_laplace_close, assert_log_density_close, assert_score_close,
                     assert_shifted_close)
 
 pytestmark = pytest.mark.gpu
@@ -472,6 +472,60 @@ def test_far_query_and_far_point(lib):
     dens, logd = P.sdkde_eval(xd, fd, h, want="both")
     assert dens.item() == 0.0 and logd.item() == float("-inf")
     assert np.all(P.sdkde_score(xd, h, points=fd).cpu().numpy() == 0.0)
+
+@pytest.mark.parametrize("flags", [0, 1, 16])
+def test_weight_sums_below_the_normal_range_are_reported_as_underflow(lib, flags):
+    """Three samples and queries up to 15 h away (found by a wider random sweep than the committed one): the GPU's
+    exp2 flushes weights below 2^-126 to zero, so with all three samples ~13.1 h from a query part of the sum was
+    lost and the log density came back finite but off by up to 0.56.  Now a sum that the flushed weights could
+    change by more than 1e-3 (below 1000 n 2^-126) is the all-underflow case (log density -inf, density 0, score
+    0), every finite result is within tolerance, and the max-shifted mode evaluates every query."""
+    P, torch = lib
+    n, m, d = 3, 1114, 12
+    x, q, h = sdkde_inputs.gaussian_mixture(n, m, d, 3, 213145, diag_cov=True)
+    h = float(h) * 1.5
+    print(f"underflow band n={n} m={m} d={d} h={h:.4f} flags={flags}", flush=True)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    dens, logd = P.sdkde_eval(xd, qd, h, want="both", flags=flags)
+    dens, logd = dens.cpu().numpy(), logd.cpu().numpy().astype(np.float64)
+    sp = P.sdkde_score(xd, h, points=qd, flags=flags).cpu().numpy()
+    ref = oracle.eval_log_density(x, q, h)
+    s_ref = oracle.score(x, h, points=q)
+    # log of the plain weight sum, and the least sum the library still trusts
+    log_sum = ref + np.log(n) + d * np.log(h) + 0.5 * d * np.log(2.0 * np.pi)
+    cut = np.log(1000.0 * n) - 126.0 * np.log(2.0)
+    fin = np.isfinite(logd)
+    if flags & 16:
+        assert fin.all()
+        assert np.max(np.abs(logd - ref)) <= TOL
+        assert_score_close(sp, s_ref, "underflow band, shifted")
+        return
+    assert 0.5 < fin.mean() < 0.95, "the case must have queries on both sides of the cut"
+    assert np.max(np.abs(logd[fin] - ref[fin])) <= TOL
+    assert np.all(log_sum[fin] > cut - 0.01) and np.all(log_sum[~fin] < cut + 0.01)
+    assert np.all(dens[~fin] == 0.0) and np.all(logd[~fin] == -np.inf)
+    clear_in, clear_out = log_sum > cut + 0.01, log_sum < cut - 0.01
+    assert np.all(sp[clear_out] == 0.0)
+    assert_score_close(sp[clear_in], s_ref[clear_in], "underflow band, score at the queries")
+
+
+@pytest.mark.parametrize("flags", [0, 1, 16])
+def test_laplace_where_the_terms_cancel_a_thousandfold(lib, flags):
+    """One 24-D Gaussian at the rule-of-thumb bandwidth (found by a wider random sweep than the committed one): the
+    samples lie 7 - 12 h from their centre, the Laplace terms of a tail query cancel to 1e-3 of their magnitude,
+    and what the fp32 Gram expansion loses in every exponent shows in the signed sum (1.4e-5 of the terms'
+    magnitude, fp32 path).  The allowance derived from that arithmetic (parity.gram_exponent_error) holds."""
+    P, torch = lib
+    n, m, d = 11437, 1036, 24
+    x, q, h = sdkde_inputs.gaussian_mixture(n, m, d, 1, 112423, diag_cov=False)
+    print(f"laplace cancellation n={n} m={m} d={d} h={h:.4f} flags={flags}", flush=True)
+    lap = P.sdkde_eval_laplace(torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda(), h, flags=flags).cpu().numpy()
+    ref, mag = oracle.eval_laplace_density(x, q, h), oracle.eval_laplace_abs_density(x, q, h)
+    kde = np.exp(oracle.eval_log_density(x, q, h))
+    assert np.min(np.abs(ref[mag >= 1e-30]) / mag[mag >= 1e-30]) < 2e-3, "the case must have cancelling sums"
+    bound = gram_exponent_error(x, q, h, low_precision_inputs=bool(flags & 15))
+    worst = assert_laplace_close(lap, ref, mag, f"laplace cancellation flags={flags}", exponent_error=bound, p_kde_ref=kde)
+    print(f"laplace cancellation flags={flags}: worst error {worst:.3g} of the allowance", flush=True)
 
 
 def test_argument_errors(lib):
