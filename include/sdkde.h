@@ -20,7 +20,10 @@
  *    strided subsample of them), which loses about (R/h)^2 * 2^-24 in the exponent of phi (R = distance of a
  *    point from that centre).  The stated 1e-3
  *    tolerances hold while R/h stays below ~100; the thin path (d <= 3, the score calls d <= 6) uses direct
- *    differences and has no such limit.  (Far outside that domain, R/h above ~1e18, the scaled
+ *    differences and has no such limit.  The score's numerator is formed the paper's way, p sum_j phi_j -
+ *    sum_j phi_j x_j, two sums of size |p - centre| sum_j phi_j carried in fp32: whatever the size of the
+ *    result, about 1e-6 (1 + R/h) / h of it is lost, which shows only where the true score is that small
+ *    against 1/h (a sample whose only neighbours are its exact duplicates).  (Far outside that domain, R/h above ~1e18, the scaled
  *    coordinates overflow fp32 on either path and the outputs are NaN.)  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
  *    is kept, and weights below the smallest normal fp32 number (2^-126) are flushed to zero: a point whose
  *    weights phi_j sum to less than 1000 n 2^-126 (so that the flushed ones could be more than one part in a
@@ -85,8 +88,10 @@ enum {
     SDKDE_PREC_FP16X2_PHI16 = 3, /* as FP16X2 for the cross term, and Phi X on the fp16 matrix units with every weight
                                rounded to ONE fp16 value (scaled by 2^14, X still hi + lo): the least precise input mode.
                                The row sums D are taken of the same rounded weights, so T - p D is exactly the direct-form
-                               numerator sum_j fp16(phi_j) (x_j - p): the error is relative to the weights (2^-11 per
-                               term, a few 1e-4 of the score of a point at worst), not to the size of the coordinates;
+                               numerator sum_j fp16(phi_j) (x_j - p): the error is relative to the weights, not to the
+                               size of the coordinates: 2^-11 per term, i.e. up to 5e-4 of sum_j phi_j |x_j - p| / (h^2 D),
+                               a few 1e-4 of the score where the terms pull one way, and up to ~1.2e-3 of it (measured)
+                               at a point with few neighbours whose pulls partly cancel;
                                fp32 accumulate, exp fp32.  Applies where FP16X2_ALL applies, and runs as FP16X2
                                elsewhere. */
     /* flags bit 4: two-pass, max-shifted sums for sdkde_eval, sdkde_eval_laplace and sdkde_score at

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import sdkde_inputs
-from parity import (TOL, gram_exponent_error, assert_density_close, assert_laplace_close, assert_log_density_close, assert_score_close,
+from parity import (TOL, gram_exponent_error, score_resolution, assert_density_close, assert_laplace_close, assert_log_density_close, assert_score_close,
                     assert_shifted_close)
 
 pytestmark = pytest.mark.gpu
@@ -526,6 +526,33 @@ def test_laplace_where_the_terms_cancel_a_thousandfold(lib, flags):
     bound = gram_exponent_error(x, q, h, low_precision_inputs=bool(flags & 15))
     worst = assert_laplace_close(lap, ref, mag, f"laplace cancellation flags={flags}", exponent_error=bound, p_kde_ref=kde)
     print(f"laplace cancellation flags={flags}: worst error {worst:.3g} of the allowance", flush=True)
+
+@pytest.mark.parametrize("d,flags,h", [(32, 0, 0.8), (32, 1, 0.8), (16, 2, 0.45), (3, 0, 0.25)])
+def test_scores_that_vanish_against_one_over_h(lib, d, flags, h):
+    """Every sample has exact duplicates and no other neighbour within reach (found by a sweep over data shapes the
+    mixtures do not have): the true score is ~1e-10 / h and below, and the paper's p D - T form of the numerator
+    cannot resolve it in fp32.  What is lost is bounded in absolute terms (parity.score_resolution), and the thin
+    path, which forms the differences directly, returns the zero."""
+    P, torch = lib
+    g = np.random.default_rng(343)
+    if d > 3:
+        base = g.standard_normal((50, d))
+    else:           # 50 distinct points of a 5 x 5 x 5 lattice with spacing 5 (20 h apart)
+        cells = g.permutation(125)[:50]
+        base = 5.0 * np.stack([cells % 5, (cells // 5) % 5, cells // 25], axis=1).astype(np.float64)
+    x = base[g.integers(0, 50, size=355)].astype(np.float32)
+    print(f"vanishing score d={d} flags={flags} h={h}", flush=True)
+    s = P.sdkde_score(torch.from_numpy(x).cuda(), h, flags=flags).cpu().numpy()
+    s_ref = oracle.score(x, h)
+    scale = np.linalg.norm(s_ref, axis=1).max() * h
+    assert scale < 1e-6, f"the case must have a vanishing score field (largest |s| h = {scale:.2e})"
+    err = np.linalg.norm(s.astype(np.float64) - s_ref, axis=1)
+    if d <= 3:
+        assert err.max() * h < 1e-12
+    else:
+        worst = float(np.max(err / score_resolution(x, x, h)))
+        print(f"vanishing score d={d} flags={flags}: largest error {err.max() * h:.2e} / h, {worst:.3g} of the resolution", flush=True)
+        assert worst <= 1.0
 
 
 def test_argument_errors(lib):
