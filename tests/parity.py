@@ -85,12 +85,14 @@ def gram_exponent_error(x, q, h, low_precision_inputs=False):
     E = (|q - c|^2 + max_j |x_j - c|^2) / 2h^2 the size of the terms that cancel, the stored norms are rounded once
     each, their sum once, and each of the d/4 MFMA steps rounds an accumulator of at most that size:
     (2 + d/4) half-ulps of E, i.e. (2 + d/4) E 2^-24.  The fp16 hi + lo input modes drop the lo.lo products,
-    2^-22 of |q~||x~| <= E per pair: four more units.  The thin path (d <= 3) forms differences directly: 0."""
+    2^-22 of |q~||x~| <= E per pair: four more units.  The thin path (d <= 3) forms the differences directly, and
+    what it rounds is the squared distance itself, d + 2 times: (2 + d) u 2^-24 with u <= 88, beyond which the weight
+    is zero in fp32."""
     x = np.asarray(x, dtype=np.float64)
     q = np.asarray(q, dtype=np.float64)
     d = x.shape[1]
     if d <= 3:
-        return np.zeros(q.shape[0])
+        return np.full(q.shape[0], (2.0 + d) * 88.0 * 2.0**-24)
     c = x.mean(axis=0)
     big = ((q - c) ** 2).sum(axis=1) + float(((x - c) ** 2).sum(axis=1).max())
     return (2.0 + d / 4.0 + (4.0 if low_precision_inputs else 0.0)) * big / (2.0 * h * h) * 2.0**-24

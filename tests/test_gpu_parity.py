@@ -509,6 +509,23 @@ def test_weight_sums_below_the_normal_range_are_reported_as_underflow(lib, flags
     assert_score_close(sp[clear_in], s_ref[clear_in], "underflow band, score at the queries")
 
 
+def test_laplace_of_a_heavy_tailed_cloud_on_the_thin_path(lib):
+    """2-D Student-t samples (3 degrees of freedom) reach 180 h from their centre; tail queries have Laplace terms that
+    cancel a thousandfold, and the direct-difference path's own rounding of the squared distance shows there (found
+    by the sweep over data shapes: 1.9 of the two-part allowance).  The derived allowance holds."""
+    P, torch = lib
+    g = np.random.default_rng(12130)
+    x = g.standard_t(3, size=(9391, 2)).astype(np.float32)
+    q = g.standard_t(3, size=(4805, 2)).astype(np.float32)
+    h = float(sdkde_inputs.silverman_bandwidth(x))
+    print(f"laplace heavy tails n={len(x)} m={len(q)} d=2 h={h:.4f}", flush=True)
+    lap = P.sdkde_eval_laplace(torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda(), h).cpu().numpy()
+    ref, mag = oracle.eval_laplace_density(x, q, h), oracle.eval_laplace_abs_density(x, q, h)
+    kde = np.exp(oracle.eval_log_density(x, q, h))
+    worst = assert_laplace_close(lap, ref, mag, "laplace heavy tails", exponent_error=gram_exponent_error(x, q, h), p_kde_ref=kde)
+    print(f"laplace heavy tails: worst error {worst:.3g} of the allowance", flush=True)
+
+
 @pytest.mark.parametrize("flags", [0, 1, 16])
 def test_laplace_where_the_terms_cancel_a_thousandfold(lib, flags):
     """One 24-D Gaussian at the rule-of-thumb bandwidth (found by a wider random sweep than the committed one): the
