@@ -17,13 +17,17 @@
  *    `flags` selects another input mode.
  *  - Accuracy domain of the matrix path (d >= 7, and the eval calls at d >= 4): squared distances are formed as
  *    |p|^2 + |x|^2 - 2 p.x on coordinates taken relative to a centre of the samples (the mean of an evenly
- *    strided subsample of them), which loses about (R/h)^2 * 2^-24 in the exponent of phi (R = distance of a
- *    point from that centre).  The stated 1e-3
- *    tolerances hold while R/h stays below ~100; the thin path (d <= 3, the score calls d <= 6) uses direct
- *    differences and has no such limit.  The score's numerator is formed the paper's way, p sum_j phi_j -
- *    sum_j phi_j x_j, two sums of size |p - centre| sum_j phi_j carried in fp32: whatever the size of the
- *    result, about 1e-6 (1 + R/h) / h of it is lost, which shows only where the true score is that small
- *    against 1/h (a sample whose only neighbours are its exact duplicates).  (Far outside that domain, R/h above ~1e18, the scaled
+ *    strided subsample of them).  With E = (|p - centre|^2 + max_j |x_j - centre|^2) / 2h^2 the size of the terms
+ *    that cancel, each of the 2 + d/4 roundings can cost E 2^-24 in the exponent of phi, so the stated 1e-3
+ *    tolerances are guaranteed while (2 + d/4) E 2^-24 <= 1e-3 (every point within about 50 h of the centre at
+ *    d = 16, 30 h at d = 64, 20 h at d = 128) and typically hold to twice those distances.  The thin path (d <= 3,
+ *    the score calls d <= 6) forms the differences directly, but of coordinates that were rounded to fp32 after
+ *    centring and scaling: a difference is good to 2^-24 R (R = distance from the centre), not to the last bit
+ *    of the inputs.  The score's numerator is formed the paper's way on the matrix path, p sum_j phi_j -
+ *    sum_j phi_j x_j, two sums of size |p - centre| sum_j phi_j carried in fp32.  On either path, whatever the
+ *    size of the result, about 1e-6 (1 + R/h) / h of the score is lost, which shows only where the true score is
+ *    that small against 1/h (a sample whose only neighbours are its exact duplicates, a bandwidth so narrow that
+ *    every neighbour's weight vanishes).  (Far outside that domain, R/h above ~1e18, the scaled
  *    coordinates overflow fp32 on either path and the outputs are NaN.)  Unless SDKDE_FLAG_MAX_SHIFT is set no running maximum
  *    is kept, and weights below the smallest normal fp32 number (2^-126) are flushed to zero: a point whose
  *    weights phi_j sum to less than 1000 n 2^-126 (so that the flushed ones could be more than one part in a
