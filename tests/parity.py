@@ -83,11 +83,11 @@ def gram_exponent_error(x, q, h, low_precision_inputs=False):
     """Bound, per query, on the absolute error of the exponent -|q - x_j|^2 / 2h^2 (in nats) as the matrix path
     forms it in fp32: |q~|^2 + |x~|^2 - 2 q~.x~ on coordinates relative to a centre c of the samples.  With
     E = (|q - c|^2 + max_j |x_j - c|^2) / 2h^2 the size of the terms that cancel, the two stored norms are rounded
-    relative to their own sizes (together at most one half-ulp of E), their sum once, and each of the d/4 MFMA steps
-    rounds an accumulator of at most that size: (2 + d/4) half-ulps of E, i.e. (2 + d/4) E 2^-24.  The fp16 hi + lo input modes drop the lo.lo products,
-    2^-22 of |q~||x~| <= E per pair: four more units.  The thin path (d <= 3) forms the differences directly, and
-    what it rounds is the squared distance itself, d + 2 times: (2 + d) u 2^-24 with u <= 88, beyond which the weight
-    is zero in fp32."""
+    relative to their own sizes (together at most one half-ulp of E), their sum once, and each of the d/4 MFMA
+    steps rounds an accumulator of at most that size: (2 + d/4) half-ulps of E, i.e. (2 + d/4) E 2^-24.  The fp16
+    hi + lo input modes drop the lo.lo products, 2^-22 of |q~||x~| <= E per pair: four more units.  The thin path
+    (d <= 3) forms the differences directly, and what it rounds is the squared distance itself, d + 2 times:
+    (2 + d) u 2^-24 with u <= 88, beyond which the weight is zero in fp32."""
     x = np.asarray(x, dtype=np.float64)
     q = np.asarray(q, dtype=np.float64)
     d = x.shape[1]
