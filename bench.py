@@ -465,7 +465,10 @@ def main():
             rec["fused_call_ms_per_step"] = fused["ms_per_step"]
             rec["fused_call_value"] = fused["value"]
             if est < 5e-3:                                           # launch-bound sizes: the same call replayed from a HIP graph
-                rec["fused_call_graph_replay_ms_per_step"], rec["graph_replay_bitwise_equal_to_eager"] = wc.graph_replay_ms(k)
+                try:
+                    rec["fused_call_graph_replay_ms_per_step"], rec["graph_replay_bitwise_equal_to_eager"] = wc.graph_replay_ms(k)
+                except Exception as e:                               # an extra: its failure must not cost the record
+                    rec["graph_replay_error"] = f"{type(e).__name__}: {e}"[:200]
             rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
             if not args.no_cpu_baseline:
                 if wc.pairs <= 4e9:                                  # a few seconds of oracle time: run it whole
