@@ -353,9 +353,9 @@ def compact(out):
             r["traffic_detail"] = {k: v for k, v in r["traffic_detail"].items() if k not in ("note", "kernel")}
         slim[key] = r
     if "other_modes" in out:
-        slim["other_modes"] = {k: _slim_run(v, with_clocks=True) for k, v in out["other_modes"].items()}
+        slim["other_modes"] = {k: (v if "error" in v else _slim_run(v, with_clocks=True)) for k, v in out["other_modes"].items()}
     if "per_config" in out:
-        slim["per_config"] = {k: _slim_run(v) for k, v in out["per_config"].items()}
+        slim["per_config"] = {k: (v if "error" in v else _slim_run(v)) for k, v in out["per_config"].items()}
     return _round(slim)
 
 
@@ -410,11 +410,14 @@ def main():
             if P.sdkde_describe_plan(n, n, d, 0, P.SDKDE_FLAG_SYMMETRIC)["symmetric"]:
                 modes.append("symmetric")
             for mode in modes:
-                rec, _ = w.run(mode_steps, 1, mode=mode)
-                rec["score_rel_frobenius_vs_fp32_path"] = float((w.s - s_fp32).norm() / s_fp32.norm())
-                rec["max_abs_log_density_diff_vs_fp32_path"] = float((w.logd - logd_fp32).abs().max())
-                rec["note"] = MODE_NOTES[mode]
-                other[mode] = rec
+                try:
+                    rec, _ = w.run(mode_steps, 1, mode=mode)
+                    rec["score_rel_frobenius_vs_fp32_path"] = float((w.s - s_fp32).norm() / s_fp32.norm())
+                    rec["max_abs_log_density_diff_vs_fp32_path"] = float((w.logd - logd_fp32).abs().max())
+                    rec["note"] = MODE_NOTES[mode]
+                    other[mode] = rec
+                except Exception as e:                               # the headline record must survive
+                    other[mode] = {"error": f"{type(e).__name__}: {e}"[:300]}
 
     paper_s = PAPER_SECONDS.get((args.config, n, m))
     sec = main_run["ms_per_step"] * 1e-3
@@ -438,7 +441,7 @@ def main():
         out["cpu_baseline"] = base
         out["parity_on_sample"] = parity_on_sample(w, ref, 0)
         for mode in other:
-            if mode in MODE_FLAGS:
+            if mode in MODE_FLAGS and "error" not in other[mode]:
                 other[mode]["parity_on_sample"] = parity_on_sample(w, ref, MODE_FLAGS[mode])
     if other:
         out["other_modes"] = other
@@ -452,41 +455,45 @@ def main():
         shapes = [(name, None, None) for name in ("C1", "C2", "C3", "C4", "C5") if name != args.config]
         shapes.append(("C2", 32768, 4096))          # the shape of the paper's runtime table
         for name, n_o, m_o in shapes:
-            wc = Workload(P, torch, sdkde_inputs, name, args.seed, n_o, m_o)
-            est = wc.pairs / 1.5e12                                  # seconds per step, roughly
-            k = int(max(3, min(200, 0.6 / max(est, 1e-6))))
-            # short steps: enough warm-up for the clocks to settle (a few hundred launches), best of three runs
-            warm = int(max(3, min(3000, 0.15 / max(est, 1e-6))))
-            tries = 3 if est < 5e-3 else 1
-            runs = [wc.run(k, warm if r == 0 else 3) for r in range(tries)]
-            rec, plan_c = min(runs, key=lambda rp: rp[0]["ms_per_step"])
-            rec["ms_per_step_of_each_run"] = [r[0]["ms_per_step"] for r in runs]
-            fused = min((wc.run(k, 3, fn=wc.fused_step)[0] for _ in range(tries)), key=lambda r: r["ms_per_step"])
-            rec["fused_call_ms_per_step"] = fused["ms_per_step"]
-            rec["fused_call_value"] = fused["value"]
-            if est < 5e-3:                                           # launch-bound sizes: the same call replayed from a HIP graph
-                try:
-                    rec["fused_call_graph_replay_ms_per_step"], rec["graph_replay_bitwise_equal_to_eager"] = wc.graph_replay_ms(k)
-                except Exception as e:                               # an extra: its failure must not cost the record
-                    rec["graph_replay_error"] = f"{type(e).__name__}: {e}"[:200]
-            rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
-            if not args.no_cpu_baseline:
-                if wc.pairs <= 4e9:                                  # a few seconds of oracle time: run it whole
-                    rec["cpu_baseline"], rec["parity_on_sample"] = oracle_whole(wc)
-                else:
-                    rec["cpu_baseline"], ref_c = oracle_sample(wc, budget_s=3.0)
-                    rec["parity_on_sample"] = parity_on_sample(wc, ref_c, 0)
-            traffic, detail = (traffic_from_profile(name, plan_c, rec["roofline"]["launch_ms"]) if (n_o is None and m_o is None)
-                               else (None, None))
-            rec["roofline"]["traffic"] = traffic
-            if detail:
-                rec["roofline"]["traffic_detail"] = detail
-            ps = PAPER_SECONDS.get((name, wc.n, wc.m))
-            if ps:
-                rec["paper_seconds_other_hardware"] = ps
-            per[name if n_o is None else f"{name}_n{wc.n}_m{wc.m}"] = rec
-            del wc
-            torch.cuda.empty_cache()
+            key = name if n_o is None else f"{name}_n{n_o}_m{m_o}"
+            try:
+                wc = Workload(P, torch, sdkde_inputs, name, args.seed, n_o, m_o)
+                est = wc.pairs / 1.5e12                                  # seconds per step, roughly
+                k = int(max(3, min(200, 0.6 / max(est, 1e-6))))
+                # short steps: enough warm-up for the clocks to settle (a few hundred launches), best of three runs
+                warm = int(max(3, min(3000, 0.15 / max(est, 1e-6))))
+                tries = 3 if est < 5e-3 else 1
+                runs = [wc.run(k, warm if r == 0 else 3) for r in range(tries)]
+                rec, plan_c = min(runs, key=lambda rp: rp[0]["ms_per_step"])
+                rec["ms_per_step_of_each_run"] = [r[0]["ms_per_step"] for r in runs]
+                fused = min((wc.run(k, 3, fn=wc.fused_step)[0] for _ in range(tries)), key=lambda r: r["ms_per_step"])
+                rec["fused_call_ms_per_step"] = fused["ms_per_step"]
+                rec["fused_call_value"] = fused["value"]
+                if est < 5e-3:                                           # launch-bound sizes: the same call replayed from a HIP graph
+                    try:
+                        rec["fused_call_graph_replay_ms_per_step"], rec["graph_replay_bitwise_equal_to_eager"] = wc.graph_replay_ms(k)
+                    except Exception as e:                               # an extra: its failure must not cost the record
+                        rec["graph_replay_error"] = f"{type(e).__name__}: {e}"[:200]
+                rec["config"] = {"n": wc.n, "m": wc.m, "d": wc.d, "h": wc.h}
+                if not args.no_cpu_baseline:
+                    if wc.pairs <= 4e9:                                  # a few seconds of oracle time: run it whole
+                        rec["cpu_baseline"], rec["parity_on_sample"] = oracle_whole(wc)
+                    else:
+                        rec["cpu_baseline"], ref_c = oracle_sample(wc, budget_s=3.0)
+                        rec["parity_on_sample"] = parity_on_sample(wc, ref_c, 0)
+                traffic, detail = (traffic_from_profile(name, plan_c, rec["roofline"]["launch_ms"]) if (n_o is None and m_o is None)
+                                   else (None, None))
+                rec["roofline"]["traffic"] = traffic
+                if detail:
+                    rec["roofline"]["traffic_detail"] = detail
+                ps = PAPER_SECONDS.get((name, wc.n, wc.m))
+                if ps:
+                    rec["paper_seconds_other_hardware"] = ps
+                per[key] = rec
+                del wc
+                torch.cuda.empty_cache()
+            except Exception as e:                                   # the headline record must survive
+                per[key] = {"error": f"{type(e).__name__}: {e}"[:300]}
         out["per_config"] = per
     print(json.dumps(out if args.verbose else compact(out), separators=(",", ":")))
 
