@@ -182,7 +182,9 @@ int sdkde_eval(const float *samples_sd, int64_t n, const float *queries, int64_t
  * The whole SD-KDE pass in one call (Method section, opening paragraph: form the empirical SD-KDE,
  * score + shift, and evaluate the resulting density on the queries): sdkde_score at the samples,
  * the shift fused into its epilogue, then sdkde_eval of the shifted samples, with the shifted samples
- * centred on the centre already computed for the samples (one launch fewer than the three calls).
+ * centred on the centre already computed for the samples (one launch fewer than the three calls; at d <= 16,
+ * where the queries' prepared copy fits beside the samples', the same epilogue also prepares the eval pass's
+ * operands: two launches fewer, same bits).
  *   samples [n, d] in      queries [m, d] in
  *   score_out [n, d] out, may be NULL      samples_sd_out [n, d] out, required
  *   density_out / log_density_out [m] out, either may be NULL, not both (unless m = 0)
@@ -239,6 +241,9 @@ int sdkde_eval_laplace(const float *samples, int64_t n, const float *queries, in
  *   [23] groups (work items = groups (groups + 1) / 2)
  * and, when out_len >= 25: [24] matrix instructions of the first contraction spent on the last 16-column block
  *   (4 = all; fewer when the block holds at most 12 real coordinates: fp32 inputs, d <= 32)
+ * and, when out_len >= 26: [25] call 2 only: 1 if sdkde_fit_eval at these sizes and flags, with a workspace of
+ *   sdkde_workspace_bytes, prepares the eval pass's operands inside its score epilogue (five launches instead
+ *   of six), else 0
  */
 int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t flags, int64_t *out,
                         int32_t out_len);
@@ -259,7 +264,9 @@ enum {
     SDKDE_TUNE_SYM_GROUPS = 5,      /* symmetric mode: most groups of sample blocks (1 .. 64) */
     SDKDE_TUNE_SYM_MIN_ITEMS = 6,   /* symmetric mode: least number of work items for the flag to take effect
                                        (default 512) */
-    SDKDE_TUNE_COUNT = 7
+    SDKDE_TUNE_SEPARATE_PREP = 7,   /* 1: sdkde_fit_eval always prepares the eval pass's operands in a launch of
+                                       its own (same results; for comparing the two forms) */
+    SDKDE_TUNE_COUNT = 8
 };
 int sdkde_set_tuning(int knob, int value);
 

@@ -23,7 +23,7 @@ SDKDE_FLAG_SYMMETRIC = 32
 SDKDE_FLAG_SAMPLES_PREPARED = 64
 SDKDE_MAX_D = 128
 (SDKDE_TUNE_SCORE_ROW_TILES, SDKDE_TUNE_SCORE_SPLITS, SDKDE_TUNE_EVAL_ROW_TILES, SDKDE_TUNE_EVAL_SPLITS,
- SDKDE_TUNE_SYM_BLOCK_ROWS, SDKDE_TUNE_SYM_GROUPS, SDKDE_TUNE_SYM_MIN_ITEMS) = range(7)
+ SDKDE_TUNE_SYM_BLOCK_ROWS, SDKDE_TUNE_SYM_GROUPS, SDKDE_TUNE_SYM_MIN_ITEMS, SDKDE_TUNE_SEPARATE_PREP) = range(8)
 SDKDE_ETOOLARGE = 5
 SDKDE_STATIC_SCRATCH_BYTES = 64 * 1024 * 1024
 
@@ -96,7 +96,7 @@ def sdkde_workspace_bytes(n: int, m: int, d: int, flags: int = SDKDE_PREC_FP32) 
 PLAN_FIELDS = ("thin", "dp", "row_tiles", "rows_per_block", "row_blocks", "splits", "tiles_per_split", "tiles",
                "n_pad", "m_pad", "workspace_bytes", "off_xs", "off_xt", "off_xn", "off_ps", "off_pn", "off_part_t",
                "off_part_d", "partial_slots", "xt_scale", "symmetric", "sym_block_rows", "sym_blocks_per_group",
-               "sym_groups", "last_block_mfmas")
+               "sym_groups", "last_block_mfmas", "fit_eval_fused_prep")
 
 
 def sdkde_describe_plan(n: int, m: int, d: int, call: int, flags: int = SDKDE_PREC_FP32) -> dict:

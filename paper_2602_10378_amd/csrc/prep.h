@@ -113,28 +113,18 @@ constexpr int kPrepRows = 32;      // rows per workgroup of prep_mfma_kernel (tw
 // followed by eight halves [lo(4g..4g+3) | the same again] (twice the bytes of the fp32 layout).
 // prec == SDKDE_PREC_FP16X2_PHI16: dst_t holds, for tile, column c and lane group g, eight halves
 // [hi(4g..4g+3) | lo(4g..4g+3)].
-// Grid: job0's blocks first (blocks0 of them), then job1's.
-__global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
-                                                           PrepCommon common, float a, int prec, Stamp stamp)
+// The body for one workgroup: rows r0 .. r0 + kPrepRows of `job`.  STAGED: the input values of those rows are
+// already in raw[][] (a caller that has just computed them); otherwise they are read from job.src.
+template <bool STAGED>
+__device__ __forceinline__ void prep_rows(const PrepJob& job, int64_t r0, int d, int dp, float a, int prec, bool poisoned,
+                                          const float* smean, float (*raw)[SDKDE_MAX_D + 1], float (*used)[SDKDE_MAX_D + 1])
 {
-    __shared__ double red[kBlock];
-    __shared__ float smean[SDKDE_MAX_D];
-    __shared__ float raw[kPrepRows][SDKDE_MAX_D + 1];     // a (x - mean)
-    __shared__ float used[kPrepRows][SDKDE_MAX_D + 1];    // the value the first contraction multiplies (hi + lo, or raw)
-    __shared__ int stamp_flag;
-    const bool poisoned = stamp_poisons(stamp, &stamp_flag);
-    prep_common(common, d, red, smean);
-
-    const bool second = (int)blockIdx.x >= blocks0;
-    const PrepJob& job = second ? job1 : job0;
-    const int64_t r0 = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kPrepRows;
     _Float16* dst_h = reinterpret_cast<_Float16*>(job.dst);
-
     for (int idx = threadIdx.x; idx < kPrepRows * dp; idx += kBlock) {
         const int rr = idx / dp, c = idx % dp;
         const int64_t row = r0 + rr;
         float v = 0.0f;
-        if (row < job.rows && c < d) v = a * (job.src[row * d + c] - smean[c]);
+        if (row < job.rows && c < d) v = a * ((STAGED ? raw[rr][c] : job.src[row * d + c]) - smean[c]);
         raw[rr][c] = v;
         if (prec != SDKDE_PREC_FP32) {
             const _Float16 hi = (_Float16)v;
@@ -183,6 +173,24 @@ __global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob
         const int64_t row = r0 + threadIdx.x;
         job.dst_n[row] = poisoned ? __builtin_nanf("") : row < job.rows ? -(float)acc : kPadNorm;
     }
+}
+
+// Grid: job0's blocks first (blocks0 of them), then job1's.
+__global__ __launch_bounds__(kBlock) void prep_mfma_kernel(PrepJob job0, PrepJob job1, int blocks0, int d, int dp,
+                                                           PrepCommon common, float a, int prec, Stamp stamp)
+{
+    __shared__ double red[kBlock];
+    __shared__ float smean[SDKDE_MAX_D];
+    __shared__ float raw[kPrepRows][SDKDE_MAX_D + 1];     // a (x - mean)
+    __shared__ float used[kPrepRows][SDKDE_MAX_D + 1];    // the value the first contraction multiplies (hi + lo, or raw)
+    __shared__ int stamp_flag;
+    const bool poisoned = stamp_poisons(stamp, &stamp_flag);
+    prep_common(common, d, red, smean);
+
+    const bool second = (int)blockIdx.x >= blocks0;
+    const PrepJob& job = second ? job1 : job0;
+    const int64_t r0 = (int64_t)(blockIdx.x - (second ? blocks0 : 0)) * kPrepRows;
+    prep_rows<false>(job, r0, d, dp, a, prec, poisoned, smean, raw, used);
 }
 
 // Thin-d variant: dst[row][d] = a (x - mean), padding rows get pad_value in every coordinate.

@@ -20,6 +20,7 @@
 #include "pair_sym.h"
 #include "pair_thin.h"
 #include "epilogue.h"
+#include "epilogue_prep.h"
 
 namespace {
 
@@ -697,11 +698,57 @@ int profile_mark(int which, int edge, hipStream_t st)
     return SDKDE_OK;
 }
 
+// What the score epilogue of sdkde_fit_eval needs in order to prepare the eval pass's operands in the same launch
+// (score_epilogue_prep_kernel): where that pass expects its prepared samples and queries, and the record it leaves.
+struct FusedPrep {
+    PrepJob sd_job, q_job;
+    Stamp stamp;
+};
+
+// Whether the one-call pass can fold the eval pass's preparation into the score epilogue, and with what.  Both passes
+// must be on the matrix path with their own full decomposition fitting the workspace, the epilogue must be the
+// four-part one, and everything the fused launch writes for the eval pass must lie where the score pass no longer
+// reads: the prepared shifted samples over the prepared samples (a workgroup reads its rows before it overwrites
+// them), their norms and the prepared queries inside the blocked transpose, which only the pair kernel reads.
+bool plan_fused_prep(const float* samples_sd, int64_t n, const float* queries, int64_t m, int32_t d, double h, void* workspace,
+                     size_t workspace_bytes, uint32_t flags, FusedPrep* out)
+{
+    if (m <= 0 || (flags & (SDKDE_FLAG_MAX_SHIFT | SDKDE_FLAG_SYMMETRIC | SDKDE_FLAG_SAMPLES_PREPARED))) return false;
+    if (tuning(SDKDE_TUNE_SEPARATE_PREP, 0) == 1) return false;
+    const uint32_t sflags = anchored_flags(flags, true);
+    Plan ps = make_plan(n, n, d, true, sflags);
+    apply_symmetric(ps, n, sflags, true);
+    const Plan pe = make_plan(n, m, d, false, flags);
+    if (ps.thin || pe.thin || ps.sym_on || ps.n_pad != pe.n_pad || ps.dp != pe.dp) return false;
+    // One workgroup of the folded launch reduces 32 rows x dp/4 items in dp/8 passes, where the plain epilogue spreads
+    // them over dp/8 workgroups: measured per pass of the whole call (folded / separate, same box), d = 16: n = 2048
+    // 28.4 / 29.9 us, 4096 33.7 / 35.7, 8192 66.2 / 67.5, 32768 x 4096 662.3 / 665.0; d = 32: 4096 50.0 / 49.1;
+    // d = 64: 4096 81.8 / 77.0; d = 128: 145.0 / 131.2.  It pays at dp = 16 only.
+    if (ps.dp != 16) return false;
+    if (effective_prec(sflags, false, ps.dp) != effective_prec(flags, false, pe.dp)) return false;
+    const Workspace ws = layout(ps, true, false, workspace, sflags);
+    const Workspace we = layout(pe, false, true, workspace, flags);
+    if (ws.bytes > workspace_bytes || we.bytes > workspace_bytes) return false;
+    if (epilogue_parts(ps.nsplit, n * (int64_t)d) != kEpiPartsFew) return false;
+    if (ps.n_pad % kPrepRows || pe.m_pad % kPrepRows || (ps.n_pad + pe.m_pad) / kPrepRows > 0x7fffffffLL) return false;
+    const char* dead_begin = (const char*)ws.xt;
+    const char* dead_end = (const char*)ws.xn;                   // the blocked transpose ends where the norms begin
+    const char* wr_begin = (const char*)we.xn;
+    const char* wr_end = (const char*)(we.pn + pe.m_pad);
+    if (we.xs != ws.xs || wr_begin < dead_begin || wr_end > dead_end) return false;
+    if ((const char*)we.ps < (const char*)(we.xn + pe.n_pad)) return false;
+    const double a = sqrt(1.4426950408889634074 / (2.0 * h * h));
+    out->sd_job = PrepJob{samples_sd, n, pe.n_pad, we.xs, nullptr, we.xn, kPadCoord};
+    out->q_job = PrepJob{queries, m, pe.m_pad, we.ps, nullptr, we.pn, 0.0f};
+    out->stamp = make_stamp(we, false, false, samples_sd, n, d, effective_prec(flags, false, pe.dp), (float)a);
+    return true;
+}
+
 // Shared body of sdkde_score and of the first half of sdkde_fit_eval.  samples_sd_out (optional, only at
 // the samples themselves): also writes samples + (h^2/2) score from the same epilogue.
 int score_impl(const float* samples, int64_t n, const float* points, int64_t m, int32_t d, double h,
                float* score_out, float* samples_sd_out, void* workspace, size_t workspace_bytes, uint32_t flags,
-               void* stream)
+               void* stream, const FusedPrep* fused = nullptr)
 {
     int rc = check_common(samples, n, m, d, h, flags);
     if (rc != SDKDE_OK) return rc;
@@ -750,6 +797,17 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
         constexpr int per_wg = kBlock / kEpiPartsFew;
         const uintptr_t io = (uintptr_t)score_out | (uintptr_t)samples_sd_out | (samples_sd_out ? (uintptr_t)samples : 0);
         const int quad_io = (d % 4 == 0 && (io & 15) == 0) ? 1 : 0;
+        if (fused) {
+            // plan_fused_prep has checked that this plan and layout are the ones it was made for
+            if (!self || !samples_sd_out || p.sym_on || mode != 2) return SDKDE_EINVAL;
+            const int blocks_sd = (int)(fused->sd_job.rows_pad / kPrepRows);
+            const int blocks_q = (int)(fused->q_job.rows_pad / kPrepRows);
+            hipLaunchKernelGGL(score_epilogue_prep_kernel, dim3((unsigned)(blocks_sd + blocks_q)), dim3(kBlock), 0, st, w.part_t,
+                               w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp, ps_halves, inv_ah2, score_out, samples, half_h2,
+                               samples_sd_out, quad_io, fused->sd_job, fused->q_job, blocks_sd,
+                               PrepCommon{nullptr, 0, w.centre}, (float)a, (int)effective_prec(flags, p.thin, p.dp), fused->stamp);
+            return hipGetLastError() == hipSuccess ? SDKDE_OK : SDKDE_EDEVICE;
+        }
         hipLaunchKernelGGL(score_epilogue_quad_kernel, dim3((unsigned)((quads + per_wg - 1) / per_wg)), dim3(kBlock), 0, st,
                            w.part_t, w.part_d, w.ps, nslots, m, p.m_pad, d, p.dp, mode, ps_halves, inv_ah2, score_out,
                            samples, half_h2, samples_sd_out, quad_io, least_trusted_sum(n));
@@ -763,7 +821,7 @@ int score_impl(const float* samples, int64_t n, const float* points, int64_t m, 
 // Shared body of sdkde_eval and sdkde_eval_laplace.
 int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
               float* density_out, float* log_density_out, void* workspace, size_t workspace_bytes, uint32_t flags,
-              void* stream, bool laplace, bool reuse_centre = false)
+              void* stream, bool laplace, bool reuse_centre = false, bool all_prepared = false)
 {
     int rc = check_common(samples, n, m, d, h, flags);
     if (rc != SDKDE_OK) return rc;
@@ -781,7 +839,9 @@ int eval_impl(const float* samples, int64_t n, const float* queries, int64_t m, 
     const bool shifted = (flags & SDKDE_FLAG_MAX_SHIFT) != 0;
     const PrepJob sample_job{samples, n, p.n_pad, w.xs, nullptr, w.xn, kPadCoord};
     const PrepJob query_job{queries, m, p.m_pad, w.ps, nullptr, w.pn, 0.0f};
-    if (flags & SDKDE_FLAG_SAMPLES_PREPARED) {
+    if (all_prepared) {
+        // sdkde_fit_eval: the score epilogue has prepared samples and queries for this plan (plan_fused_prep)
+    } else if (flags & SDKDE_FLAG_SAMPLES_PREPARED) {
         // the workspace still holds the centre and the prepared samples (their place in the workspace depends
         // on n, d and the precision mode only, not on m): only the queries are prepared
         // (a call whose record of the prepared samples does not match gets NaN for every output)
@@ -871,12 +931,17 @@ int sdkde_fit_eval(const float* samples, int64_t n, const float* queries, int64_
     int rc = check_common(samples, n, m, d, h, flags);
     if (rc != SDKDE_OK) return rc;
     if (m > 0 && (!queries || (!density_out && !log_density_out))) return SDKDE_EINVAL;
-    rc = score_impl(samples, n, nullptr, n, d, h, score_out, samples_sd_out, workspace, workspace_bytes, flags, stream);
+    if (!workspace || ((uintptr_t)workspace & 255)) return SDKDE_EWORKSPACE;
+    // The centre of the samples stays in the workspace; the shifted samples are centred on it too (any
+    // centre is exact, it only has to be near the data).  Where the layouts allow it the score epilogue also
+    // prepares the eval pass's operands: five launches instead of six.
+    FusedPrep fused;
+    const bool fuse = plan_fused_prep(samples_sd_out, n, queries, m, d, h, workspace, workspace_bytes, flags, &fused);
+    rc = score_impl(samples, n, nullptr, n, d, h, score_out, samples_sd_out, workspace, workspace_bytes, flags, stream,
+                    fuse ? &fused : nullptr);
     if (rc != SDKDE_OK || m == 0) return rc;
-    // The centre of the samples is still in the workspace; the shifted samples are centred on it too (any
-    // centre is exact, it only has to be near the data).
     return eval_impl(samples_sd_out, n, queries, m, d, h, density_out, log_density_out, workspace, workspace_bytes,
-                     flags, stream, false, true);
+                     flags, stream, false, true, fuse);
 }
 
 int sdkde_fit_eval_static(const float* samples, int64_t n, const float* queries, int64_t m, int32_t d, double h,
@@ -953,6 +1018,13 @@ int sdkde_describe_plan(int64_t n, int64_t m, int32_t d, int32_t call, uint32_t 
     if (out_len >= 25)
         out[24] = (!p.thin && partial_last_block_built(p.dp / 16, score ? kScoreSelf : kEval, (int)effective_prec(flags, p.thin, p.dp)))
                       ? p.klast : 4;
+    if (out_len >= 26) {
+        out[25] = 0;
+        size_t need = 0;
+        FusedPrep unused;
+        if (call == 2 && sdkde_workspace_bytes(n, m, d, flags, &need) == SDKDE_OK)
+            out[25] = plan_fused_prep(nullptr, n, nullptr, m, d, 1.0, base, need, flags, &unused) ? 1 : 0;
+    }
     return SDKDE_OK;
 }
 

@@ -353,6 +353,36 @@ def test_fused_call_matches_oracle_and_three_calls(lib, n, m, d, seed):
     x_sd2, _, logd2 = P.sdkde_fit_eval(xd, qd, h, want="log")
     assert torch.equal(x_sd2, x_sd) and torch.equal(logd2, logd)
 
+@pytest.mark.parametrize("n,m,d,flags", [(4096, 1024, 16, 0), (3000, 333, 16, 0), (2048, 512, 9, 0), (1333, 77, 13, 0),
+                                          (5000, 1, 7, 0), (3000, 700, 16, 1), (4096, 1024, 16, 2), (4096, 1024, 16, 3),
+                                          (20000, 3000, 12, 0), (70000, 9000, 16, 0)])
+def test_one_call_pass_with_and_without_the_folded_preparation(lib, tuning, n, m, d, flags):
+    """sdkde_fit_eval prepares the eval pass's operands inside its score epilogue where the layouts allow it; with the
+    knob that keeps the preparation in a launch of its own every output has the same bits, and the record the
+    folded launch leaves lets a later SDKDE_FLAG_SAMPLES_PREPARED call reuse the prepared shifted samples."""
+    P, torch = lib
+    print(f"folded preparation n={n} m={m} d={d} flags={flags}", flush=True)
+    assert P.sdkde_describe_plan(n, m, d, 2, flags)["fit_eval_fused_prep"] == 1
+    x, q, h = _mixture(n, m, d, 91)
+    xd, qd = torch.from_numpy(x).cuda(), torch.from_numpy(q).cuda()
+    ws = P.make_workspace(n, m, d)
+    outs = []
+    for separate in (0, 1):
+        tuning(P.SDKDE_TUNE_SEPARATE_PREP, separate)
+        s = torch.full_like(xd, float("nan"))
+        x_sd, dens, logd = P.sdkde_fit_eval(xd, qd, h, score_out=s, want="both", workspace=ws, flags=flags)
+        if separate == 0:
+            # the prepared shifted samples and their record are those of an eval call on x_sd
+            _, again = P.sdkde_eval(x_sd, qd, h, want="log", workspace=ws, flags=flags | P.SDKDE_FLAG_SAMPLES_PREPARED)
+            assert torch.equal(again, logd)
+        outs.append([t.clone() for t in (s, x_sd, dens, logd)])
+    for a, b, what in zip(outs[0], outs[1], ("score", "shifted samples", "density", "log density")):
+        assert torch.isfinite(a).all() and torch.equal(a, b), f"{what} differs between the two forms"
+    s_ref, x_sd_ref, logp_ref = oracle.sd_kde_log_density(x, q, h)
+    if flags == 0:
+        assert_score_close(outs[0][0].cpu().numpy(), s_ref, "folded preparation")
+    assert_log_density_close(outs[0][3].cpu().numpy(), logp_ref, "folded preparation")
+
 
 def test_single_sample_closed_form(lib):
     # n = 1: s(p) = -(p - x1)/h^2 exactly as in the paper's score formula.

@@ -165,10 +165,26 @@ def test_tuning_overrides_change_the_plan_and_are_validated(tuning):
         assert P.sdkde_describe_plan(65536, 65536, 16, 0) == base
     finally:
         del os.environ["SDKDE_SCORE_SPLIT"]
-    for knob, value in ((-1, 1), (P.SDKDE_TUNE_SYM_MIN_ITEMS + 1, 1), (0, -5)):
+    for knob, value in ((-1, 1), (P.SDKDE_TUNE_SEPARATE_PREP + 1, 1), (0, -5)):
         with pytest.raises(P.SdkdeError) as e:
             P.sdkde_set_tuning(knob, value)
         assert e.value.status == 1
+
+def test_one_call_pass_folds_the_eval_preparation_where_the_layouts_allow(tuning):
+    """sdkde_fit_eval prepares the eval pass's operands inside its score epilogue when both passes are on the matrix
+    path with d <= 16 and what that launch writes fits where the score pass no longer reads (the prepared queries must fit inside
+    the samples' blocked transpose): reported by sdkde_describe_plan, switched off by its tuning knob."""
+    fused = lambda n, m, d, flags=0: P.sdkde_describe_plan(n, m, d, 2, flags)["fit_eval_fused_prep"]
+    assert fused(4096, 1024, 16) == 1 and fused(1048576, 131072, 16) == 1 and fused(32768, 4096, 16) == 1
+    assert fused(5000, 700, 9) == 1
+    assert fused(262144, 65536, 64) == 0 and fused(5000, 700, 20) == 0      # measured: it pays at dp = 16 only
+    assert fused(4096, 1024, 16, P.SDKDE_PREC_FP16X2) == 1 and fused(4096, 1024, 16, P.SDKDE_PREC_FP16X2_PHI16) == 1
+    assert fused(32768, 32768, 16) == 0                    # as many queries as samples: no room for them
+    assert fused(32768, 65536, 1) == 0 and fused(3000, 500, 5) == 0      # thin path (either pass)
+    assert fused(4096, 1024, 16, P.SDKDE_FLAG_MAX_SHIFT) == 0 and fused(65536, 1024, 16, P.SDKDE_FLAG_SYMMETRIC) == 0
+    assert P.sdkde_describe_plan(4096, 1024, 16, 0)["fit_eval_fused_prep"] == 0     # a property of the eval call's plan
+    tuning(P.SDKDE_TUNE_SEPARATE_PREP, 1)
+    assert fused(4096, 1024, 16) == 0
 
 
 def test_library_is_rebuilt_when_a_source_changes(tmp_path, monkeypatch):
